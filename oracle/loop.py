@@ -1,0 +1,65 @@
+"""Outer LSP loop (Algorithm 1 lines 3-11) on the CPU oracle.  TEST
+INFRASTRUCTURE ONLY (see oracle/lsp_oracle.c).
+
+Each iteration asks the caller for this step's logits over the still-active
+rows, takes id / margin (Eq. 1), finds and snaps the boundary, commits and
+appends, until no sequence has an active position left.  It also counts top-1
+flips (Section 4.3.4): positions that are still active at step k and whose
+top-1 id differs from the one they had at step k-1.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import commit, confidence
+
+
+def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
+                prefix_len, suffix_len, tokens, kv_layers=None, max_steps=100000, trace=False):
+    """logits_fn(step, prefix_len) -> [B,S,V] CPU tensor (row u = u-th active position).
+    prefix_len / suffix_len / tokens / kv_layers (list of dicts with k_suf,
+    v_suf, k_cache, v_cache; the suffix tensors are indexed by ABSOLUTE
+    generation position, row 0 = first generated position) are updated in place.
+    Returns dict(steps, flips, flip_denominator, committed, per_step=[...])."""
+    B = prefix_len.shape[0]
+    P0 = prefix_len.clone()
+    G = int(suffix_len.max())
+    prev = torch.full((B, G), -1, dtype=torch.int64)
+    steps = flips = denom = committed = 0
+    per_step = []
+    while int(suffix_len.max()) > 0:
+        assert steps < max_steps
+        z = logits_fn(steps, prefix_len)
+        ids, prob, mar = confidence(z, suffix_len)
+        S = ids.shape[1]
+        done = (prefix_len - P0).long()
+        for b in range(B):
+            n = int(suffix_len[b])
+            cur = ids[b, :n].long()
+            old = prev[b, done[b]:done[b] + n]
+            seen = old >= 0
+            flips += int(((cur != old) & seen).sum())
+            denom += int(seen.sum())
+            prev[b, done[b]:done[b] + n] = cur
+        kw = {}
+        if kv_layers is not None:
+            # this step's suffix K/V rows = absolute rows [done_b, done_b + S) of each sequence
+            ks, vs = [], []
+            for L in kv_layers:
+                k = torch.zeros((B, S) + L["k_suf"].shape[2:], dtype=L["k_suf"].dtype)
+                v = torch.zeros_like(k)
+                for b in range(B):
+                    n = int(suffix_len[b])
+                    k[b, :n] = L["k_suf"][b, done[b]:done[b] + n]
+                    v[b, :n] = L["v_suf"][b, done[b]:done[b] + n]
+                ks.append(k)
+                vs.append(v)
+            kw = dict(k_suf=ks, v_suf=vs, k_cache=[L["k_cache"] for L in kv_layers],
+                      v_cache=[L["v_cache"] for L in kv_layers])
+        out = commit(mar, ids, bitmap, V, tau, window, min_commit, snap_enabled,
+                     prefix_len, suffix_len, tokens=tokens, C=tokens.shape[1], **kw)
+        committed += int(out["commit_len"].sum())
+        if trace:
+            per_step.append({k: v.clone() for k, v in out.items()} | {"ids": ids, "margin": mar, "prob": prob})
+        steps += 1
+    return dict(steps=steps, flips=flips, flip_denominator=denom, committed=committed, per_step=per_step)
