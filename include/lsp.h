@@ -1,0 +1,204 @@
+/*
+ * liblsp - per-denoising-step hot path of the Longest Stable Prefix (LSP)
+ * scheduler for diffusion language models, for AMD MI355X (gfx950).
+ *
+ * One scheduler iteration (Algorithm 1, lines 4-10 of the paper) is three
+ * calls:
+ *   lsp_attn_step   attention of the active-suffix queries over
+ *                   [committed-prefix KV cache || suffix K/V]   (line 4)
+ *   lsp_confidence  top-1 id, logit margin (Eq. 1) and top-1 probability of
+ *                   every active position                       (line 5)
+ *   lsp_commit      stability mask, longest stable prefix L'(tau), snap to the
+ *                   last delimiter, fallback, commit and contiguous KV append
+ *                                                               (lines 7-10)
+ *
+ * Conventions
+ *  - Plain C ABI.  Every pointer documented as "device" is GPU memory owned by
+ *    the caller; the library never allocates, frees or keeps it.  Pointers
+ *    documented as "host" are read during the call only.
+ *  - Every call validates its arguments on the host first; on an error nothing
+ *    is launched.  Work is enqueued on `stream` (a hipStream_t passed as
+ *    void*, NULL = the default stream) and the call returns without
+ *    synchronising: outputs are valid in stream order.
+ *  - Sequence state lives on the device: prefix_len[b] (rows of sequence b in
+ *    the cache, P_b) and suffix_len[b] (active positions, N_b).  No call reads
+ *    them on the host, so a step needs no device-to-host transfer.
+ *  - Element types: LSP_F32 (IEEE binary32) and LSP_BF16 (bfloat16).
+ *  - Dense layouts, innermost dimension contiguous:
+ *      suffix Q / O     [B, S, Hq,  D]
+ *      suffix K / V     [B, S, Hkv, D]      row u = u-th active position
+ *      cache  K / V     [B, C, Hkv, D]      per layer, token-major, so the rows
+ *                                           committed in one step form ONE
+ *                                           contiguous block per sequence
+ *      logits           [B, S, V]
+ *    Strides (in elements) may be given for the outer dimensions.
+ *  - Return value: LSP_OK or a negative lsp_status; lsp_last_error() gives a
+ *    text for the calling thread's last failure.
+ */
+#ifndef LSP_H
+#define LSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LSP_F32 = 0, LSP_BF16 = 1 } lsp_dtype;
+
+typedef enum {
+  LSP_OK = 0,
+  LSP_ERR_INVALID_ARG = -1, /* null pointer, bad dimension, misaligned pointer or stride */
+  LSP_ERR_UNSUPPORTED = -2, /* dtype / head_dim combination that is not built */
+  LSP_ERR_WORKSPACE = -3,   /* workspace missing or smaller than lsp_*_workspace_bytes */
+  LSP_ERR_HIP = -4          /* the HIP runtime refused a launch */
+} lsp_status;
+
+/* Bits of status_flags[b] written by lsp_commit. */
+#define LSP_FLAG_CACHE_FULL 1  /* commit length was cut to the cache room C - P_b */
+#define LSP_FLAG_TOKENS_FULL 2 /* commit length was cut to the token buffer room T - P_b */
+
+const char *lsp_version(void);
+const char *lsp_last_error(void);
+
+/* ------------------------------------------------------------------------- *
+ * Suffix attention (Algorithm 1 line 4; Section 3.2 "bidirectional lookahead"
+ * and "approximate KV caching for prefix states").
+ *
+ * For every sequence b, query head h and active row i < N_b:
+ *     O[b,i,h,:] = softmax_t( scale * Q[b,i,h,:] . K*[t,g,:] ) . V*[t,g,:]
+ * where t runs over the P_b cached rows and then the N_b suffix rows, no mask
+ * of any kind, and g = h / (Hq/Hkv).  Rows i >= N_b of O are not written.
+ * Sequences with N_b = 0 cost nothing.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+  int32_t dtype;          /* lsp_dtype of Q, K, V and O */
+  int32_t B, S, Hq, Hkv;  /* S = rows of the suffix buffers */
+  int32_t D;              /* head dim: 64 or 128 */
+  int32_t C;              /* cache capacity in rows */
+  float scale;            /* soft-max scale; 0 selects 1/sqrt(D) */
+  /* element strides of (batch, row, head); all three 0 selects the dense default */
+  int64_t q_stride[3];
+  int64_t kv_suf_stride[3];
+  int64_t cache_stride[3];
+  int64_t o_stride[3];
+} lsp_attn_desc;
+
+size_t lsp_attn_workspace_bytes(const lsp_attn_desc *desc);
+
+/*
+ * q, k_suf, v_suf, k_cache, v_cache, out: device, 16-byte aligned, strides
+ * multiples of 16 bytes.  prefix_len, suffix_len: device int32[B], with
+ * 0 <= P_b <= C and 0 <= N_b <= S (not checked on the host; values are
+ * clamped to those ranges on the device).  workspace: device, at least
+ * lsp_attn_workspace_bytes(desc) bytes, 256-byte aligned (may be NULL when
+ * that size is 0).
+ */
+int32_t lsp_attn_step(const lsp_attn_desc *desc, const void *q, const void *k_suf,
+                      const void *v_suf, const void *k_cache, const void *v_cache,
+                      const int32_t *prefix_len, const int32_t *suffix_len, void *out,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- *
+ * Per-position confidence (Eq. 1; Algorithm 1 line 5).
+ *
+ * For every sequence b and active row i < N_b, over the row z = logits[b,i,:]:
+ *     top1_id  = the lowest index attaining max_v z[v]
+ *     margin   = z_(1) - z_(2), one fp32 subtraction, where z_(2) is the
+ *                largest entry other than top1_id (so 0 on a tied maximum)
+ *     top1_prob= 1 / sum_v exp(z[v] - z_(1))        (fp32 accumulation)
+ * Rows i >= N_b are neither read nor written.  Precondition: the row maximum
+ * is finite and the row holds no NaN (-inf entries are fine).
+ * ------------------------------------------------------------------------- */
+size_t lsp_confidence_workspace_bytes(int32_t B, int32_t S, int32_t V);
+
+/*
+ * logits: device, element type `dtype`; row (b,i) starts at element
+ * b*batch_stride + i*row_stride (0 selects the dense S*V / V).  Any alignment
+ * of at least the element size is accepted; 16-byte aligned rows take the fast
+ * path.  suffix_len: device int32[B] or NULL (= all S rows active).
+ * top1_id (int32), top1_prob (fp32), margin (fp32): device, [B,S] dense.
+ */
+int32_t lsp_confidence(int32_t dtype, const void *logits, int32_t B, int32_t S, int32_t V,
+                       int64_t row_stride, int64_t batch_stride, const int32_t *suffix_len,
+                       int32_t *top1_id, float *top1_prob, float *margin,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- *
+ * Boundary search, snap, commit and append (Section 3.2: L'(tau), the snap
+ * equation and the monotone-progress fallback; Algorithm 1 lines 7-10).
+ *
+ * Per sequence b, with N = N_b and P = P_b on entry:
+ *   stable_mask[b,i] = (i < N and margin[b,i] > tau)           (strict)
+ *   raw_boundary[b]  = L' = first i with stable_mask = 0, else N
+ *   snapped_boundary = the largest length j in [1, L'] with L' - j <= window
+ *                      whose last token top1_id[b,j-1] is in the delimiter
+ *                      set; L' when there is none, when snap_enabled = 0 or
+ *                      when L' = 0.  window < 0 = no limit.
+ *   commit_len[b]    = L = min(N, max(snapped_boundary, min_commit)), cut to
+ *                      the cache room C - P and the token room T - P (a cut
+ *                      sets the matching LSP_FLAG_* bit in status_flags[b]).
+ *   tokens[b, P..P+L) = top1_id[b, 0..L)
+ *   for every layer: cache rows [P, P+L) = suffix rows [0, L), K and V - one
+ *                      contiguous block of L*Hkv*D elements each
+ *   prefix_len[b] = P + L ; suffix_len[b] = N - L
+ * ------------------------------------------------------------------------- */
+typedef struct {
+  int32_t kv_dtype;       /* lsp_dtype of the K/V buffers */
+  int32_t B, S, V;
+  int32_t Hkv, D, C;      /* K/V row = Hkv*D contiguous elements; its byte size must be a multiple of 16 */
+  int32_t num_layers;     /* 0 = boundary search and token commit only */
+  int32_t T;              /* length of one sequence's token buffer */
+  float tau;              /* margin threshold, logit units; +-inf allowed */
+  int32_t window;         /* W */
+  int32_t min_commit;     /* L_min >= 0 */
+  int32_t snap_enabled;
+  int64_t suf_batch_stride;   /* elements between sequences in a suffix K/V buffer; 0 = S*Hkv*D */
+  int64_t cache_batch_stride; /* elements between sequences in a cache; 0 = C*Hkv*D */
+} lsp_commit_desc;
+
+size_t lsp_commit_workspace_bytes(const lsp_commit_desc *desc);
+
+/*
+ * margin (fp32), top1_id (int32): device [B,S], as written by lsp_confidence.
+ * delimiter_bitmap: device uint32[ceil(V/32)], bit (v%32) of word v/32 set
+ * when id v is a delimiter.  Ids outside [0,V) are treated as non-delimiters.
+ * k_suf_layers, v_suf_layers, k_cache_layers, v_cache_layers: HOST arrays of
+ * num_layers DEVICE pointers (read during the call; may all be NULL when
+ * num_layers = 0).  Buffers 16-byte aligned; a cache must not overlap the
+ * suffix buffers.
+ * tokens: device int32 [B,T] in/out, or NULL.  prefix_len, suffix_len: device
+ * int32[B] in/out.  stable_mask: device uint8 [B,S].  raw_boundary,
+ * snapped_boundary, commit_len, status_flags: device int32[B] out
+ * (status_flags may be NULL).
+ */
+int32_t lsp_commit(const lsp_commit_desc *desc, const float *margin, const int32_t *top1_id,
+                   const uint32_t *delimiter_bitmap,
+                   const void *const *k_suf_layers, const void *const *v_suf_layers,
+                   void *const *k_cache_layers, void *const *v_cache_layers,
+                   int32_t *tokens, int32_t *prefix_len, int32_t *suffix_len,
+                   uint8_t *stable_mask, int32_t *raw_boundary, int32_t *snapped_boundary,
+                   int32_t *commit_len, int32_t *status_flags,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- *
+ * Flip bookkeeping for a decode loop (Section 4.3.4: share of active-suffix
+ * positions whose top-1 prediction changes between consecutive steps).
+ *
+ * Call once per step after lsp_confidence and BEFORE lsp_commit.  last_id
+ * [B,G] holds, per generation position (0 = first generated token), the top-1
+ * id it had at the previous step, or -1.  With done_b = prefix_len[b] -
+ * base_prefix_len[b], for u < N_b: position j = done_b + u; if last_id[b,j] >=
+ * 0 then counters[1] += 1 and counters[0] += (last_id[b,j] != top1_id[b,u]);
+ * then last_id[b,j] = top1_id[b,u].  counters: device int64[2] accumulated.
+ * ------------------------------------------------------------------------- */
+int32_t lsp_flip_update(const int32_t *top1_id, int32_t B, int32_t S, int32_t G,
+                        const int32_t *prefix_len, const int32_t *suffix_len,
+                        const int32_t *base_prefix_len, int32_t *last_id,
+                        int64_t *counters, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSP_H */

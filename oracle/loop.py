@@ -18,8 +18,8 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
                 prefix_len, suffix_len, tokens, kv_layers=None, max_steps=100000, trace=False):
     """logits_fn(step, prefix_len) -> [B,S,V] CPU tensor (row u = u-th active position).
     prefix_len / suffix_len / tokens / kv_layers (list of dicts with k_suf,
-    v_suf, k_cache, v_cache; the suffix tensors are indexed by ABSOLUTE
-    generation position, row 0 = first generated position) are updated in place.
+    v_suf [B,S,Hkv,D], row u = u-th active position, reused unchanged by every
+    step, and k_cache, v_cache) are updated in place.
     Returns dict(steps, flips, flip_denominator, committed, per_step=[...])."""
     B = prefix_len.shape[0]
     P0 = prefix_len.clone()
@@ -31,7 +31,6 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
         assert steps < max_steps
         z = logits_fn(steps, prefix_len)
         ids, prob, mar = confidence(z, suffix_len)
-        S = ids.shape[1]
         done = (prefix_len - P0).long()
         for b in range(B):
             n = int(suffix_len[b])
@@ -43,19 +42,8 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
             prev[b, done[b]:done[b] + n] = cur
         kw = {}
         if kv_layers is not None:
-            # this step's suffix K/V rows = absolute rows [done_b, done_b + S) of each sequence
-            ks, vs = [], []
-            for L in kv_layers:
-                k = torch.zeros((B, S) + L["k_suf"].shape[2:], dtype=L["k_suf"].dtype)
-                v = torch.zeros_like(k)
-                for b in range(B):
-                    n = int(suffix_len[b])
-                    k[b, :n] = L["k_suf"][b, done[b]:done[b] + n]
-                    v[b, :n] = L["v_suf"][b, done[b]:done[b] + n]
-                ks.append(k)
-                vs.append(v)
-            kw = dict(k_suf=ks, v_suf=vs, k_cache=[L["k_cache"] for L in kv_layers],
-                      v_cache=[L["v_cache"] for L in kv_layers])
+            kw = dict(k_suf=[L["k_suf"] for L in kv_layers], v_suf=[L["v_suf"] for L in kv_layers],
+                      k_cache=[L["k_cache"] for L in kv_layers], v_cache=[L["v_cache"] for L in kv_layers])
         out = commit(mar, ids, bitmap, V, tau, window, min_commit, snap_enabled,
                      prefix_len, suffix_len, tokens=tokens, C=tokens.shape[1], **kw)
         committed += int(out["commit_len"].sum())

@@ -1,0 +1,221 @@
+"""Python binding of liblsp (the LSP per-step hot path for MI355X).
+
+Argument marshalling only: every function takes torch tensors that already
+live on the GPU, passes their pointers and the current HIP stream to the C-ABI
+entry point of the same name (include/lsp.h) and returns the output tensors.
+There is no fallback: importing works without the built library (so that the
+package can be inspected), but the first call raises if liblsp.so is missing.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblsp.so")
+_lib = None
+
+LSP_F32, LSP_BF16 = 0, 1
+FLAG_CACHE_FULL, FLAG_TOKENS_FULL = 1, 2
+
+
+class LspError(RuntimeError):
+    pass
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("S", ctypes.c_int32),
+                ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("C", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("q_stride", ctypes.c_int64 * 3), ("kv_suf_stride", ctypes.c_int64 * 3),
+                ("cache_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3)]
+
+
+class CommitDesc(ctypes.Structure):
+    _fields_ = [("kv_dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("S", ctypes.c_int32),
+                ("V", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("C", ctypes.c_int32), ("num_layers", ctypes.c_int32), ("T", ctypes.c_int32),
+                ("tau", ctypes.c_float), ("window", ctypes.c_int32), ("min_commit", ctypes.c_int32),
+                ("snap_enabled", ctypes.c_int32), ("suf_batch_stride", ctypes.c_int64),
+                ("cache_batch_stride", ctypes.c_int64)]
+
+
+EXPORTS = ["lsp_version", "lsp_last_error", "lsp_attn_workspace_bytes", "lsp_attn_step",
+           "lsp_confidence_workspace_bytes", "lsp_confidence", "lsp_commit_workspace_bytes",
+           "lsp_commit", "lsp_flip_update"]
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises LspError when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise LspError(f"{LIB_PATH} is missing: run `python -m paper_2603_05454_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        L.lsp_version.restype = ctypes.c_char_p
+        L.lsp_last_error.restype = ctypes.c_char_p
+        for n in ("lsp_attn_workspace_bytes", "lsp_confidence_workspace_bytes", "lsp_commit_workspace_bytes"):
+            getattr(L, n).restype = ctypes.c_size_t
+        for n in ("lsp_attn_step", "lsp_confidence", "lsp_commit", "lsp_flip_update"):
+            getattr(L, n).restype = ctypes.c_int32
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise LspError(f"{what} failed with status {rc}: {lib().lsp_last_error().decode()}")
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return LSP_F32
+    if t.dtype == torch.bfloat16:
+        return LSP_BF16
+    raise LspError(f"unsupported element type {t.dtype}")
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise LspError("liblsp takes device tensors only")
+
+
+def version() -> str:
+    return lib().lsp_version().decode()
+
+
+def _strides3(t):
+    assert t.stride(3) == 1, "innermost dimension must be contiguous"
+    return (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+
+def attn_workspace_bytes(dtype, B, S, Hq, Hkv, D, C) -> int:
+    d = AttnDesc(dtype=dtype, B=B, S=S, Hq=Hq, Hkv=Hkv, D=D, C=C)
+    return lib().lsp_attn_workspace_bytes(ctypes.byref(d))
+
+
+def attn_step(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len, scale=0.0, out=None,
+              workspace=None):
+    """lsp_attn_step: q [B,S,Hq,D], k_suf/v_suf [B,S,Hkv,D], caches [B,C,Hkv,D],
+    prefix_len/suffix_len int32 [B].  Returns out [B,S,Hq,D] (same dtype as q);
+    rows >= suffix_len[b] are not written."""
+    _dev(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len)
+    B, S, Hq, D = q.shape
+    if out is None:
+        out = torch.empty((B, S, Hq, D), dtype=q.dtype, device=q.device)
+    d = AttnDesc(dtype=_dtype(q), B=B, S=S, Hq=Hq, Hkv=k_suf.shape[2], D=D, C=k_cache.shape[1],
+                 scale=float(scale))
+    d.q_stride = _strides3(q)
+    d.kv_suf_stride = _strides3(k_suf)
+    assert v_suf.stride() == k_suf.stride() and v_cache.stride() == k_cache.stride()
+    d.cache_stride = _strides3(k_cache)
+    d.o_stride = _strides3(out)
+    need = lib().lsp_attn_workspace_bytes(ctypes.byref(d))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().lsp_attn_step(ctypes.byref(d), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_cache),
+                             _ptr(v_cache), _ptr(prefix_len), _ptr(suffix_len), _ptr(out),
+                             _ptr(workspace), ctypes.c_size_t(wb), _stream())
+    _check(rc, "lsp_attn_step")
+    return out
+
+
+def confidence_workspace_bytes(B, S, V) -> int:
+    return lib().lsp_confidence_workspace_bytes(B, S, V)
+
+
+def confidence(logits, suffix_len=None, out=None, workspace=None):
+    """lsp_confidence: logits [B,S,V] -> (top1_id int32, top1_prob f32, margin f32), [B,S]."""
+    _dev(logits, suffix_len)
+    B, S, V = logits.shape
+    assert logits.stride(2) == 1
+    if out is None:
+        out = (torch.empty((B, S), dtype=torch.int32, device=logits.device),
+               torch.empty((B, S), dtype=torch.float32, device=logits.device),
+               torch.empty((B, S), dtype=torch.float32, device=logits.device))
+    need = lib().lsp_confidence_workspace_bytes(B, S, V)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=logits.device)
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().lsp_confidence(_dtype(logits), _ptr(logits), B, S, V,
+                              ctypes.c_int64(logits.stride(1)), ctypes.c_int64(logits.stride(0)),
+                              _ptr(suffix_len), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]),
+                              _ptr(workspace), ctypes.c_size_t(wb), _stream())
+    _check(rc, "lsp_confidence")
+    return out
+
+
+class LayerTable:
+    """Host arrays of per-layer device pointers, built once and reused."""
+
+    def __init__(self, k_suf, v_suf, k_cache, v_cache):
+        n = len(k_suf)
+        assert len(v_suf) == len(k_cache) == len(v_cache) == n
+        for lst in (k_suf, v_suf, k_cache, v_cache):
+            for t in lst:
+                _dev(t)
+                assert t.is_contiguous() or (t.stride(3) == 1 and t.stride(2) == t.shape[3]
+                                             and t.stride(1) == t.shape[2] * t.shape[3])
+        Arr = ctypes.c_void_p * n
+        self.n = n
+        self.arrays = [Arr(*[t.data_ptr() for t in lst]) for lst in (k_suf, v_suf, k_cache, v_cache)]
+        self.keep = (k_suf, v_suf, k_cache, v_cache)
+        self.kv_dtype = _dtype(k_suf[0])
+        self.S, self.Hkv, self.D = k_suf[0].shape[1:]
+        self.C = k_cache[0].shape[1]
+        self.suf_bs = k_suf[0].stride(0)
+        self.cache_bs = k_cache[0].stride(0)
+
+
+def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
+           prefix_len, suffix_len, tokens=None, layers: LayerTable | None = None, C=None, out=None):
+    """lsp_commit.  Mutates tokens, prefix_len, suffix_len and the caches of
+    `layers` in place.  Returns dict(stable_mask, raw_boundary, snapped_boundary,
+    commit_len, status_flags)."""
+    _dev(margin, top1_id, bitmap, prefix_len, suffix_len, tokens)
+    B, S = margin.shape
+    dev = margin.device
+    if out is None:
+        out = {"stable_mask": torch.empty((B, S), dtype=torch.uint8, device=dev)}
+        for k in ("raw_boundary", "snapped_boundary", "commit_len", "status_flags"):
+            out[k] = torch.empty(B, dtype=torch.int32, device=dev)
+    d = CommitDesc(B=B, S=S, V=V, tau=float(tau), window=int(window), min_commit=int(min_commit),
+                   snap_enabled=int(snap_enabled), T=0 if tokens is None else tokens.shape[1])
+    if layers is not None:
+        assert layers.S == S
+        d.kv_dtype, d.Hkv, d.D, d.C, d.num_layers = layers.kv_dtype, layers.Hkv, layers.D, layers.C, layers.n
+        d.suf_batch_stride, d.cache_batch_stride = layers.suf_bs, layers.cache_bs
+        arrs = layers.arrays
+    else:
+        assert C is not None
+        d.C, d.num_layers = C, 0
+        arrs = [ctypes.c_void_p(0)] * 4
+    rc = lib().lsp_commit(ctypes.byref(d), _ptr(margin), _ptr(top1_id), _ptr(bitmap),
+                          arrs[0], arrs[1], arrs[2], arrs[3], _ptr(tokens), _ptr(prefix_len),
+                          _ptr(suffix_len), _ptr(out["stable_mask"]), _ptr(out["raw_boundary"]),
+                          _ptr(out["snapped_boundary"]), _ptr(out["commit_len"]),
+                          _ptr(out["status_flags"]), ctypes.c_void_p(0), ctypes.c_size_t(0), _stream())
+    _check(rc, "lsp_commit")
+    return out
+
+
+def flip_update(top1_id, prefix_len, suffix_len, base_prefix_len, last_id, counters):
+    """lsp_flip_update: accumulate counters (int64[2]: flips, positions compared)."""
+    _dev(top1_id, prefix_len, suffix_len, base_prefix_len, last_id, counters)
+    B, S = top1_id.shape
+    rc = lib().lsp_flip_update(_ptr(top1_id), B, S, last_id.shape[1], _ptr(prefix_len), _ptr(suffix_len),
+                               _ptr(base_prefix_len), _ptr(last_id), _ptr(counters), _stream())
+    _check(rc, "lsp_flip_update")

@@ -1,0 +1,211 @@
+// lsp_commit: stability mask, longest stable prefix L'(tau), snap to the last
+// delimiter inside the look-back window, L_min / fallback, token commit and the
+// contiguous KV-cache append (Section 3.2 of the paper; Algorithm 1 lines 7-10).
+//
+// Two kernels.  The boundary kernel runs one workgroup per sequence: every
+// wave ballots "unstable" over its 64 positions, the first set bit of the first
+// non-empty ballot is that wave's candidate, and an LDS minimum across waves
+// gives L'.  The delimiter search walks back from L' through the window with
+// one lane per candidate length and an LDS maximum.  The append kernel then
+// copies, per (layer, K|V, sequence), the single contiguous block of
+// L * Hkv * D elements from the suffix buffer to cache row P with 16-byte
+// loads and stores; the block length is read from device memory, so the host
+// never learns L and the grid is sized for the worst case with early exit.
+#include "lsp_common.h"
+
+namespace lsp {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kScanThreads = 256;
+
+__global__ __launch_bounds__(kScanThreads) void boundary_kernel(
+    const float *__restrict__ margin, const int32_t *__restrict__ top1_id,
+    const uint32_t *__restrict__ bitmap, int S, int V, int C, int T, float tau, int window,
+    int min_commit, int snap_enabled, int32_t *__restrict__ tokens,
+    int32_t *__restrict__ prefix_len, int32_t *__restrict__ suffix_len,
+    uint8_t *__restrict__ stable_mask, int32_t *__restrict__ raw_boundary,
+    int32_t *__restrict__ snapped_boundary, int32_t *__restrict__ commit_len,
+    int32_t *__restrict__ status_flags) {
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
+  __shared__ int s_first, s_snap;
+  const int N = min(max(suffix_len[b], 0), S);
+  const int P = max(prefix_len[b], 0);
+  const float *mg = margin + int64_t(b) * S;
+  const int32_t *id = top1_id + int64_t(b) * S;
+  uint8_t *mk = stable_mask + int64_t(b) * S;
+  if (tid == 0) {
+    s_first = N;
+    s_snap = 0;
+  }
+  __syncthreads();
+
+  // mask + first unstable position
+  int first = N;
+  for (int base = 0; base < S; base += kScanThreads) {
+    const int i = base + tid;
+    const bool in = i < N;
+    const bool stable = in && mg[i] > tau;
+    if (i < S) mk[i] = stable ? 1 : 0;
+    const unsigned long long bal = __ballot(in && !stable);
+    if (bal != 0ull && first == N) first = i - lane + __builtin_ctzll(bal);
+  }
+  if (lane == 0 && first < N) atomicMin(&s_first, first);
+  __syncthreads();
+  const int Lp = s_first;
+
+  // last delimiter inside the window: candidate lengths j = Lp, Lp-1, ...
+  if (snap_enabled && Lp > 0) {
+    const int lo = window < 0 ? 1 : max(1, Lp - window);
+    int best = 0;
+    for (int j = Lp - tid; j >= lo; j -= kScanThreads) {
+      const int32_t v = id[j - 1];
+      const bool d = unsigned(v) < unsigned(V) && ((bitmap[v >> 5] >> (v & 31)) & 1u);
+      if (d) {
+        best = j;
+        break;  // a lane's candidates only get shorter from here
+      }
+    }
+    if (best > 0) atomicMax(&s_snap, best);
+  }
+  __syncthreads();
+  const int Ls = s_snap > 0 ? s_snap : Lp;
+  int L = min(N, max(Ls, min_commit));
+  int flag = 0;
+  if (L > C - P) {
+    L = max(C - P, 0);
+    flag |= LSP_FLAG_CACHE_FULL;
+  }
+  if (tokens != nullptr && L > T - P) {
+    L = max(T - P, 0);
+    flag |= LSP_FLAG_TOKENS_FULL;
+  }
+  if (tokens != nullptr)
+    for (int i = tid; i < L; i += kScanThreads) tokens[int64_t(b) * T + P + i] = id[i];
+  if (tid == 0) {
+    raw_boundary[b] = Lp;
+    snapped_boundary[b] = Ls;
+    commit_len[b] = L;
+    if (status_flags != nullptr) status_flags[b] = flag;
+    prefix_len[b] = P + L;
+    suffix_len[b] = N - L;
+  }
+}
+
+constexpr int kMaxLayersPerLaunch = 32;
+struct LayerPtrs {
+  const char *src[2 * kMaxLayersPerLaunch];  // K then V per layer
+  char *dst[2 * kMaxLayersPerLaunch];
+};
+
+constexpr int kCopyThreads = 256;
+constexpr int kCopyVecs = 4;  // 16-byte vectors per thread
+constexpr int kCopyBytes = kCopyThreads * kCopyVecs * 16;
+
+// grid: (chunks of kCopyBytes covering S rows, B, 2 * layers in this launch).
+// prefix_len already holds P + L; the block starts at row P = prefix_len - L.
+__global__ __launch_bounds__(kCopyThreads) void append_kernel(
+    LayerPtrs ptrs, int64_t row_bytes, int64_t suf_batch_bytes, int64_t cache_batch_bytes,
+    const int32_t *__restrict__ prefix_len, const int32_t *__restrict__ commit_len) {
+  const int b = blockIdx.y;
+  const int L = commit_len[b];
+  const int64_t total = int64_t(L) * row_bytes;
+  const int64_t off0 = int64_t(blockIdx.x) * kCopyBytes;
+  if (off0 >= total) return;
+  const int P = prefix_len[b] - L;
+  const char *src = ptrs.src[blockIdx.z] + int64_t(b) * suf_batch_bytes;
+  char *dst = ptrs.dst[blockIdx.z] + int64_t(b) * cache_batch_bytes + int64_t(P) * row_bytes;
+  u32x4 v[kCopyVecs];
+#pragma unroll
+  for (int k = 0; k < kCopyVecs; ++k) {
+    const int64_t o = off0 + (int64_t(k) * kCopyThreads + threadIdx.x) * 16;
+    if (o < total) v[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
+  }
+#pragma unroll
+  for (int k = 0; k < kCopyVecs; ++k) {
+    const int64_t o = off0 + (int64_t(k) * kCopyThreads + threadIdx.x) * 16;
+    if (o < total) __builtin_nontemporal_store(v[k], reinterpret_cast<u32x4 *>(dst + o));
+  }
+}
+
+}  // namespace
+}  // namespace lsp
+
+extern "C" size_t lsp_commit_workspace_bytes(const lsp_commit_desc *) { return 0; }
+
+extern "C" int32_t lsp_commit(const lsp_commit_desc *d, const float *margin, const int32_t *top1_id,
+                              const uint32_t *delimiter_bitmap,
+                              const void *const *k_suf_layers, const void *const *v_suf_layers,
+                              void *const *k_cache_layers, void *const *v_cache_layers,
+                              int32_t *tokens, int32_t *prefix_len, int32_t *suffix_len,
+                              uint8_t *stable_mask, int32_t *raw_boundary,
+                              int32_t *snapped_boundary, int32_t *commit_len,
+                              int32_t *status_flags, void *workspace, size_t workspace_bytes,
+                              void *stream) {
+  using namespace lsp;
+  (void)workspace;
+  (void)workspace_bytes;
+  LSP_CHECK_ARG(d != nullptr, "lsp_commit: null descriptor");
+  LSP_CHECK_ARG(margin && top1_id && prefix_len && suffix_len && stable_mask && raw_boundary &&
+                    snapped_boundary && commit_len,
+                "lsp_commit: null pointer");
+  LSP_CHECK_ARG(d->B > 0 && d->S > 0 && d->V >= 2 && d->C > 0, "lsp_commit: bad B/S/V/C");
+  LSP_CHECK_ARG(d->B <= 65535, "lsp_commit: B must be <= 65535");
+  LSP_CHECK_ARG(d->min_commit >= 0, "lsp_commit: min_commit must be >= 0");
+  LSP_CHECK_ARG(d->tau == d->tau, "lsp_commit: tau is NaN");
+  LSP_CHECK_ARG(!d->snap_enabled || delimiter_bitmap, "lsp_commit: snapping needs a delimiter bitmap");
+  LSP_CHECK_ARG(tokens == nullptr || d->T > 0, "lsp_commit: token buffer needs T > 0");
+  LSP_CHECK_ARG(d->num_layers >= 0, "lsp_commit: num_layers < 0");
+  int64_t row_bytes = 0, suf_bb = 0, cache_bb = 0;
+  if (d->num_layers > 0) {
+    LSP_CHECK_ARG(d->kv_dtype == LSP_F32 || d->kv_dtype == LSP_BF16, "lsp_commit: unknown kv_dtype");
+    LSP_CHECK_ARG(d->Hkv > 0 && d->D > 0, "lsp_commit: bad Hkv/D");
+    LSP_CHECK_ARG(k_suf_layers && v_suf_layers && k_cache_layers && v_cache_layers,
+                  "lsp_commit: null layer pointer table");
+    const int64_t es = int64_t(elem_size(d->kv_dtype));
+    row_bytes = int64_t(d->Hkv) * d->D * es;
+    LSP_CHECK_ARG(row_bytes % 16 == 0, "lsp_commit: K/V row of %lld bytes is not a multiple of 16", (long long)row_bytes);
+    suf_bb = (d->suf_batch_stride ? d->suf_batch_stride : int64_t(d->S) * d->Hkv * d->D) * es;
+    cache_bb = (d->cache_batch_stride ? d->cache_batch_stride : int64_t(d->C) * d->Hkv * d->D) * es;
+    LSP_CHECK_ARG(suf_bb % 16 == 0 && cache_bb % 16 == 0 && suf_bb >= int64_t(d->S) * row_bytes &&
+                      cache_bb >= int64_t(d->C) * row_bytes,
+                  "lsp_commit: bad batch strides");
+    for (int l = 0; l < d->num_layers; ++l) {
+      LSP_CHECK_ARG(k_suf_layers[l] && v_suf_layers[l] && k_cache_layers[l] && v_cache_layers[l],
+                    "lsp_commit: null K/V pointer in layer %d", l);
+      LSP_CHECK_ARG(aligned16(k_suf_layers[l]) && aligned16(v_suf_layers[l]) &&
+                        aligned16(k_cache_layers[l]) && aligned16(v_cache_layers[l]),
+                    "lsp_commit: K/V pointer of layer %d is not 16-byte aligned", l);
+    }
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  boundary_kernel<<<d->B, kScanThreads, 0, st>>>(
+      margin, top1_id, delimiter_bitmap, d->S, d->V, d->C, d->T, d->tau, d->window, d->min_commit,
+      d->snap_enabled, tokens, prefix_len, suffix_len, stable_mask, raw_boundary, snapped_boundary,
+      commit_len, status_flags);
+  LSP_CHECK_LAUNCH("lsp_commit: boundary launch");
+  if (d->num_layers > 0) {
+    const int64_t max_bytes = int64_t(d->S) * row_bytes;
+    const unsigned chunks = unsigned((max_bytes + kCopyBytes - 1) / kCopyBytes);
+    for (int l0 = 0; l0 < d->num_layers; l0 += kMaxLayersPerLaunch) {
+      const int nl = d->num_layers - l0 < kMaxLayersPerLaunch ? d->num_layers - l0 : kMaxLayersPerLaunch;
+      LayerPtrs p;
+      for (int l = 0; l < nl; ++l) {
+        p.src[2 * l] = static_cast<const char *>(k_suf_layers[l0 + l]);
+        p.src[2 * l + 1] = static_cast<const char *>(v_suf_layers[l0 + l]);
+        p.dst[2 * l] = static_cast<char *>(k_cache_layers[l0 + l]);
+        p.dst[2 * l + 1] = static_cast<char *>(v_cache_layers[l0 + l]);
+      }
+      for (int l = 2 * nl; l < 2 * kMaxLayersPerLaunch; ++l) {
+        p.src[l] = nullptr;
+        p.dst[l] = nullptr;
+      }
+      append_kernel<<<dim3(chunks, d->B, 2 * nl), kCopyThreads, 0, st>>>(p, row_bytes, suf_bb, cache_bb,
+                                                                         prefix_len, commit_len);
+      LSP_CHECK_LAUNCH("lsp_commit: append launch");
+    }
+  }
+  return LSP_OK;
+}

@@ -1,0 +1,70 @@
+// Library-wide pieces of liblsp: error text, version, flip bookkeeping.
+#include <stdarg.h>
+
+#include "lsp_common.h"
+
+namespace lsp {
+
+static thread_local char g_error[512] = "";
+
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+}
+
+namespace {
+
+// Section 4.3.4 flip bookkeeping: one workgroup per sequence; a position counts
+// when it already had a prediction at the previous step.
+__global__ __launch_bounds__(256) void flip_kernel(
+    const int32_t *__restrict__ top1_id, int S, int G, const int32_t *__restrict__ prefix_len,
+    const int32_t *__restrict__ suffix_len, const int32_t *__restrict__ base_prefix_len,
+    int32_t *__restrict__ last_id, unsigned long long *__restrict__ counters) {
+  const int b = blockIdx.x;
+  const int N = min(max(suffix_len[b], 0), S);
+  const int done = prefix_len[b] - base_prefix_len[b];
+  int flips = 0, seen = 0;
+  for (int u = threadIdx.x; u < N; u += blockDim.x) {
+    const int j = done + u;
+    if (j < 0 || j >= G) continue;
+    const int32_t cur = top1_id[int64_t(b) * S + u];
+    const int32_t old = last_id[int64_t(b) * G + j];
+    if (old >= 0) {
+      ++seen;
+      flips += (old != cur);
+    }
+    last_id[int64_t(b) * G + j] = cur;
+  }
+#pragma unroll
+  for (int m = 1; m < kWave; m <<= 1) {
+    flips += __shfl_xor(flips, m);
+    seen += __shfl_xor(seen, m);
+  }
+  if ((threadIdx.x & (kWave - 1)) == 0 && seen > 0) {
+    atomicAdd(&counters[0], (unsigned long long)flips);
+    atomicAdd(&counters[1], (unsigned long long)seen);
+  }
+}
+
+}  // namespace
+}  // namespace lsp
+
+extern "C" const char *lsp_version(void) { return "liblsp 0.1 (gfx950)"; }
+extern "C" const char *lsp_last_error(void) { return lsp::g_error; }
+
+extern "C" int32_t lsp_flip_update(const int32_t *top1_id, int32_t B, int32_t S, int32_t G,
+                                   const int32_t *prefix_len, const int32_t *suffix_len,
+                                   const int32_t *base_prefix_len, int32_t *last_id,
+                                   int64_t *counters, void *stream) {
+  using namespace lsp;
+  LSP_CHECK_ARG(top1_id && prefix_len && suffix_len && base_prefix_len && last_id && counters,
+                "lsp_flip_update: null pointer");
+  LSP_CHECK_ARG(B > 0 && S > 0 && G > 0, "lsp_flip_update: bad B/S/G");
+  flip_kernel<<<B, 256, 0, static_cast<hipStream_t>(stream)>>>(
+      top1_id, S, G, prefix_len, suffix_len, base_prefix_len, last_id,
+      reinterpret_cast<unsigned long long *>(counters));
+  LSP_CHECK_LAUNCH("lsp_flip_update: launch");
+  return LSP_OK;
+}

@@ -1,0 +1,52 @@
+"""Outer LSP loop (Algorithm 1 lines 3-11) on the HIP library.
+
+Host side of the scheduler: per iteration it obtains the step's logits from
+the caller (the stand-in for the denoiser), runs lsp_confidence, the flip
+bookkeeping and lsp_commit, optionally lsp_attn_step per layer, and stops when
+no sequence has an active position left.  The only device-to-host traffic is
+the termination test, polled every `poll` steps.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import LayerTable, attn_step, commit, confidence, flip_update
+
+
+def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
+                prefix_len, suffix_len, tokens, kv_layers=None, gen_len=None, run_attention=False,
+                poll=1, max_steps=100000):
+    """logits_fn(step, prefix_len) -> device logits [B,S,V].  prefix_len,
+    suffix_len, tokens and the caches in kv_layers (list of dicts q?, k_suf,
+    v_suf, k_cache, v_cache) are updated in place.  Returns dict(steps, flips,
+    flip_denominator, committed)."""
+    dev = prefix_len.device
+    B = prefix_len.shape[0]
+    G = int(gen_len if gen_len is not None else suffix_len.max().item())
+    base = prefix_len.clone()
+    last_id = torch.full((B, G), -1, dtype=torch.int32, device=dev)
+    counters = torch.zeros(2, dtype=torch.int64, device=dev)
+    table = None
+    if kv_layers is not None:
+        table = LayerTable([L["k_suf"] for L in kv_layers], [L["v_suf"] for L in kv_layers],
+                           [L["k_cache"] for L in kv_layers], [L["v_cache"] for L in kv_layers])
+    steps = 0
+    out = conf = None
+    attn_out = None
+    while True:
+        if steps % poll == 0 and int(suffix_len.max().item()) == 0:
+            break
+        assert steps < max_steps
+        if run_attention and kv_layers is not None:
+            for L in kv_layers:
+                attn_out = attn_step(L["q"], L["k_suf"], L["v_suf"], L["k_cache"], L["v_cache"],
+                                     prefix_len, suffix_len, out=attn_out)
+        z = logits_fn(steps, prefix_len)
+        conf = confidence(z, suffix_len, out=conf)
+        flip_update(conf[0], prefix_len, suffix_len, base, last_id, counters)
+        out = commit(conf[2], conf[0], bitmap, V, tau, window, min_commit, snap_enabled,
+                     prefix_len, suffix_len, tokens=tokens, layers=table, C=tokens.shape[1], out=out)
+        steps += 1
+    c = counters.tolist()
+    committed = int((prefix_len - base).sum().item())
+    return dict(steps=steps, flips=c[0], flip_denominator=c[1], committed=committed)

@@ -1,0 +1,128 @@
+"""GPU parity: lsp_attn_step against the CPU oracle (Algorithm 1 line 4;
+Section 3.2).  Max abs error <= 1e-5 (fp32) / 2e-2 (bf16)."""
+import pytest
+import torch
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def lsp():
+    import paper_2603_05454_amd as m
+    assert torch.cuda.is_available()
+    return m
+
+
+def _run(lsp, kv, pl, sl, scale=0.0):
+    g = {k: v.cuda() for k, v in kv.items()}
+    out = torch.full(g["q"].shape, 123.0, dtype=g["q"].dtype, device="cuda")
+    lsp.attn_step(g["q"], g["k_suf"], g["v_suf"], g["k_cache"], g["v_cache"], pl.cuda(), sl.cuda(),
+                  scale=scale, out=out)
+    torch.cuda.synchronize()
+    return out.float().cpu()
+
+
+def _check_full(lsp, oracle, w, pl, sl, scale=0.0, layer=0):
+    kv = W.make_layer_kv(w, layer, prefix_len=pl)
+    got = _run(lsp, kv, pl, sl, scale)
+    ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl, scale=scale or None)
+    act = ~torch.isnan(ref)
+    err = (got[act] - ref[act]).abs().max().item() if act.any() else 0.0
+    assert err <= TOL[w.dtype], err
+    assert torch.all(got[~act] == 123.0)          # rows >= suffix_len untouched
+    return err
+
+
+def test_c1_tiny_fp32(lsp, oracle):
+    pl, sl = W.make_lengths(W.C1)
+    _check_full(lsp, oracle, W.C1, pl, sl)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (6, 2), (7, 1)])
+def test_ragged_lengths_gqa(lsp, oracle, dtype, D, Hq, Hkv):
+    """Per-sequence lengths as a decode loop leaves them: an empty suffix, an
+    empty prefix, lengths that are not multiples of any tile."""
+    w = W.scaled(W.C2, dtype=dtype, B=4, S=150, P=200, C=256, Hq=Hq, Hkv=Hkv, D=D, seed=7 + D + Hq)
+    pl = torch.tensor([200, 0, 77, 131], dtype=torch.int32)
+    sl = torch.tensor([150, 129, 0, 1], dtype=torch.int32)
+    _check_full(lsp, oracle, w, pl, sl)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_single_key_and_tile_edges(lsp, oracle, dtype):
+    w = W.scaled(W.C2, dtype=dtype, B=6, S=130, P=70, C=128, Hq=2, Hkv=2, D=128, seed=21)
+    pl = torch.tensor([0, 63, 64, 65, 128, 0], dtype=torch.int32)
+    sl = torch.tensor([1, 1, 64, 63, 128, 130], dtype=torch.int32)
+    _check_full(lsp, oracle, w, pl, sl)
+
+
+def test_explicit_scale(lsp, oracle):
+    w = W.scaled(W.C2, B=1, S=64, P=64, C=64, Hq=2, Hkv=1, D=128, seed=5)
+    pl, sl = W.make_lengths(w)
+    _check_full(lsp, oracle, w, pl, sl, scale=0.05)
+
+
+def test_cache_rows_beyond_prefix_are_never_read(lsp):
+    """Poison (and NaN) beyond prefix_len must not reach the output."""
+    w = W.scaled(W.C2, B=2, S=96, P=100, C=256, Hq=2, Hkv=2, D=128, seed=9)
+    pl = torch.tensor([100, 37], dtype=torch.int32)
+    sl = torch.tensor([96, 50], dtype=torch.int32)
+    kv = W.make_layer_kv(w, 0, prefix_len=pl)
+    a = _run(lsp, kv, pl, sl)
+    kv["k_cache"][0, 100:] = float("nan")
+    kv["v_cache"][1, 37:] = float("nan")
+    kv["k_suf"][1, 50:] = float("nan")
+    kv["v_suf"][1, 50:] = float("nan")
+    b = _run(lsp, kv, pl, sl)
+    assert torch.equal(a, b) and not torch.isnan(b).any()
+
+
+def test_strided_views(lsp, oracle):
+    """Q/K/V sliced out of a fused [B,S,3H,D] projection buffer."""
+    w = W.scaled(W.C2, B=2, S=70, P=40, C=64, Hq=4, Hkv=4, D=128, seed=13)
+    pl, sl = W.make_lengths(w)
+    kv = W.make_layer_kv(w, 0)
+    fused = torch.cat([kv["q"], kv["k_suf"], kv["v_suf"]], dim=2).cuda()
+    q, k, v = fused[:, :, 0:4], fused[:, :, 4:8], fused[:, :, 8:12]
+    out = lsp.attn_step(q, k, v, kv["k_cache"].cuda(), kv["v_cache"].cuda(), pl.cuda(), sl.cuda())
+    torch.cuda.synchronize()
+    ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl)
+    assert (out.float().cpu() - ref).abs().max().item() <= 2e-2
+
+
+def test_c2_full_size(lsp, oracle):
+    pl, sl = W.make_lengths(W.C2)
+    err = _check_full(lsp, oracle, W.C2, pl, sl)
+    print("c2 attention max abs err", err)
+
+
+def _sampled(lsp, oracle, w, n=96, seed=3, layer=0):
+    kv = W.make_layer_kv(w, layer, device="cuda")
+    pl, sl = W.make_lengths(w)
+    out = lsp.attn_step(kv["q"], kv["k_suf"], kv["v_suf"], kv["k_cache"], kv["v_cache"], pl.cuda(), sl.cuda())
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(seed)
+    rows = torch.stack([torch.randint(0, w.B, (n,), generator=g), torch.randint(0, w.S, (n,), generator=g),
+                        torch.randint(0, w.Hq, (n,), generator=g)], dim=1).to(torch.int32)
+    rows[0] = torch.tensor([0, 0, 0]); rows[1] = torch.tensor([w.B - 1, w.S - 1, w.Hq - 1])
+    ref = oracle.attention(**{k: v.cpu() for k, v in kv.items()}, prefix_len=pl, suffix_len=sl, rows=rows)
+    got = out[rows[:, 0].long().cuda(), rows[:, 1].long().cuda(), rows[:, 2].long().cuda()].float().cpu()
+    err = (got - ref).abs().max().item()
+    assert err <= 2e-2, err
+    # property on every row: outputs are convex combinations of V rows
+    vmax = max(kv["v_suf"].float().abs().max().item(), kv["v_cache"][:, : w.P].float().abs().max().item())
+    assert out.float().abs().max().item() <= vmax and not torch.isnan(out.float()).any()
+    return err
+
+
+def test_c3_gqa_sampled(lsp, oracle):
+    _sampled(lsp, oracle, W.C3)
+
+
+def test_c4_shape_one_layer_sampled(lsp, oracle):
+    _sampled(lsp, oracle, W.C4, n=64, layer=5)
