@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Benchmark of the LSP per-step hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic input:
+lsp_attn_step for every layer of the workload, lsp_confidence over the logits,
+lsp_commit (boundary search + snap + token commit + KV append for every layer).
+Inputs are resident in HBM before the timed region.  To keep the Infinity Cache
+from serving re-reads, steps rotate over several independent input sets whose
+total size exceeds 256 MB, and every step gets fresh (prefix_len, suffix_len)
+arrays so that no restore kernel sits in the timed region.
+
+Prints ONE JSON line (see the field list at the bottom of this file).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+MALL_BYTES = 256 << 20
+
+# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (summaries under profiles/); None where no counter run has been made.
+MEASURED_TRAFFIC = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", type=int, default=1, help="replay the step from a HIP graph (1) or launch eagerly (0)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU; --gpus {args.gpus} is not supported "
+              "(every box has one MI355X and the path has no multi-GPU leg)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2603_05454_amd as lsp
+    import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = {"c1": W.C1, "c2": W.C2, "c3": W.C3, "c4": W.C4}[args.workload]
+    if args.layers:
+        w = W.scaled(w, layers=args.layers)
+    K, Wm = args.steps, args.warmup
+    es = W.elem_bytes(w)
+
+    # ---- input sets ------------------------------------------------------------
+    kv_bytes_layer = (w.B * w.S * (w.Hq + 2 * w.Hkv) * w.D + 2 * w.B * w.C * w.Hkv * w.D) * es
+    set_bytes = w.B * w.S * w.V * es + w.layers * kv_bytes_layer
+    R = max(1, min(8, -(-3 * MALL_BYTES // set_bytes)))       # >= 768 MB in rotation when sets are small
+    sets = []
+    _, bitmap = W.make_delimiters(w)
+    bitmap = bitmap.to(dev)
+    for r in range(R):
+        wr = W.scaled(w, seed=w.seed + 101 * r)
+        z, _ = W.make_logits(wr, device=dev)
+        layers = [W.make_layer_kv(wr, l, device=dev) for l in range(w.layers)]
+        table = lsp.LayerTable([L["k_suf"] for L in layers], [L["v_suf"] for L in layers],
+                               [L["k_cache"] for L in layers], [L["v_cache"] for L in layers])
+        sets.append(dict(z=z, layers=layers, table=table, tokens=W.make_tokens(wr, w.C).to(dev),
+                         attn_out=torch.empty_like(layers[0]["q"])))
+    pl0, sl0 = W.make_lengths(w, device=dev)
+    n_state = K + Wm
+    PL = pl0.repeat(n_state + 1, 1).contiguous()
+    SL = sl0.repeat(n_state + 1, 1).contiguous()
+    conf_out = (torch.empty((w.B, w.S), dtype=torch.int32, device=dev),
+                torch.empty((w.B, w.S), dtype=torch.float32, device=dev),
+                torch.empty((w.B, w.S), dtype=torch.float32, device=dev))
+    commit_out = []
+    for _ in range(n_state + 1):
+        o = {"stable_mask": torch.empty((w.B, w.S), dtype=torch.uint8, device=dev)}
+        for k in ("raw_boundary", "snapped_boundary", "commit_len", "status_flags"):
+            o[k] = torch.zeros(w.B, dtype=torch.int32, device=dev)
+        commit_out.append(o)
+    ws_bytes = max(lsp.confidence_workspace_bytes(w.B, w.S, w.V),
+                   lsp.attn_workspace_bytes(lsp.LSP_BF16 if w.dtype == "bf16" else lsp.LSP_F32, w.B, w.S, w.Hq, w.Hkv, w.D, w.C), 256)
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def attn(s, pl, sl):
+        for L in s["layers"]:
+            lsp.attn_step(L["q"], L["k_suf"], L["v_suf"], L["k_cache"], L["v_cache"], pl, sl,
+                          out=s["attn_out"], workspace=workspace)
+
+    def conf(s, sl):
+        lsp.confidence(s["z"], sl, out=conf_out, workspace=workspace)
+
+    def commit(s, pl, sl, out):
+        lsp.commit(conf_out[2], conf_out[0], bitmap, w.V, w.tau, w.window, w.min_commit, 1, pl, sl,
+                   tokens=s["tokens"], layers=s["table"], out=out)
+
+    def step(i):
+        s = sets[i % R]
+        attn(s, PL[i], SL[i])
+        conf(s, SL[i])
+        commit(s, PL[i], SL[i], commit_out[i])
+
+    # ---- whole-step timing --------------------------------------------------------
+    for i in range(Wm):
+        step(i)
+    torch.cuda.synchronize()
+    graph = None
+    if args.graph:
+        # capture the K timed steps once (each has its own state arrays), replay inside the timed region
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(Wm, Wm + K):
+                step(i)
+        torch.cuda.synchronize()
+        # capture does not execute: the state arrays of the timed steps are still untouched
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(Wm, Wm + K):
+            step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / K
+    committed = int(sum(int(commit_out[i]["commit_len"].sum().item()) for i in range(Wm, Wm + K)))
+    value = committed / wall
+
+    # ---- per-call timing (HIP events on the launch stream, back to back) ----------
+    def time_call(fn, reps):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(reps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / reps
+
+    reps = max(20, min(K, 200))
+    scratch_pl, scratch_sl = PL[n_state], SL[n_state]
+
+    def reset_state():
+        scratch_pl.copy_(pl0)
+        scratch_sl.copy_(sl0)
+
+    t_attn = time_call(lambda i: attn(sets[i % R], pl0, sl0), reps) / max(1, w.layers)
+    t_conf = time_call(lambda i: conf(sets[i % R], sl0), reps)
+    # the commit mutates its state arrays: time it on scratch copies, restoring between calls
+    # (the two tiny copies are timed separately and subtracted)
+    t_copy = time_call(lambda i: reset_state(), reps)
+    conf(sets[0], sl0)
+
+    def commit_once(i):
+        reset_state()
+        commit(sets[0], scratch_pl, scratch_sl, commit_out[n_state])
+
+    t_commit = max(time_call(commit_once, reps) - t_copy, 0.0)
+
+    L0 = commit_out[n_state]["commit_len"].sum().item()
+    conf_bytes = w.B * w.S * (w.V * es + 12)
+    flops_layer = W.attn_flops(w)
+    append_bytes = 2 * L0 * w.Hkv * w.D * es * 2 * w.layers
+    kernels = {
+        "lsp_attn_step": {"s": t_attn, "bound": "mfma", "achieved": flops_layer / t_attn / 1e12,
+                          "peak": MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else 157.3, "unit": "TFLOP/s"},
+        "lsp_confidence": {"s": t_conf, "bound": "hbm", "achieved": conf_bytes / t_conf / 1e9,
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s"},
+        "lsp_commit": {"s": t_commit, "bound": "hbm", "achieved": append_bytes / max(t_commit, 1e-9) / 1e9,
+                       "peak": HBM_PEAK_GBS, "unit": "GB/s"},
+    }
+    share = {"lsp_attn_step": t_attn * w.layers, "lsp_confidence": t_conf, "lsp_commit": t_commit}
+    dom = max(share, key=share.get)
+    kd = kernels[dom]
+    roofline = {"kernel": dom, "bound": kd["bound"], "achieved": round(kd["achieved"], 2), "peak": kd["peak"],
+                "unit": kd["unit"], "frac": round(kd["achieved"] / kd["peak"], 4),
+                "traffic": MEASURED_TRAFFIC.get((args.workload, dom)),
+                "avg_launch_us": round(kd["s"] * 1e6, 2),
+                "all": {k: {"avg_us": round(v["s"] * 1e6, 2), "achieved": round(v["achieved"], 2), "unit": v["unit"],
+                            "frac": round(v["achieved"] / v["peak"], 4)} for k, v in kernels.items()}}
+
+    # ---- oracle on the host cores ---------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        s = sets[0]
+        nl = min(w.layers, 1)
+        hz = s["z"].cpu()
+        hl = [{k: v.cpu() for k, v in L.items()} for L in s["layers"][:nl]]
+        bm = bitmap.cpu()
+        pl, sl, tok = pl0.cpu().clone(), sl0.cpu().clone(), s["tokens"].cpu().clone()
+        # attention rows: every row when the layer is small, else a seeded sample scaled up
+        total_rows = w.B * w.S * w.Hq
+        n_rows = total_rows if W.attn_flops(w) < 8e9 else 4096
+        g = torch.Generator().manual_seed(1)
+        rows = None
+        if n_rows < total_rows:
+            rows = torch.stack([torch.randint(0, w.B, (n_rows,), generator=g), torch.randint(0, w.S, (n_rows,), generator=g),
+                                torch.randint(0, w.Hq, (n_rows,), generator=g)], 1).to(torch.int32)
+        # confidence rows: all when < 64M logits, else the first rows up to that
+        zr = hz if hz.numel() <= (64 << 20) else hz[:, : max(1, (64 << 20) // (w.B * w.V))].contiguous()
+        c0 = time.perf_counter()
+        for L in hl:
+            oracle.attention(L["q"], L["k_suf"], L["v_suf"], L["k_cache"], L["v_cache"], pl, sl, rows=rows)
+        c1 = time.perf_counter()
+        ids_r, p_r, m_r = oracle.confidence(zr)
+        c2 = time.perf_counter()
+        if zr.shape[1] != w.S:      # commit needs all rows: fill the rest from the GPU result
+            ids_f, m_f = conf_out[0].cpu(), conf_out[2].cpu()
+            ids_f[:, : zr.shape[1]] = ids_r
+            m_f[:, : zr.shape[1]] = m_r
+            ids_r, m_r = ids_f, m_f
+        c3 = time.perf_counter()
+        oc = oracle.commit(m_r, ids_r, bm, w.V, w.tau, w.window, w.min_commit, 1, pl, sl, tokens=tok,
+                           k_suf=[L["k_suf"] for L in hl], v_suf=[L["v_suf"] for L in hl],
+                           k_cache=[L["k_cache"] for L in hl], v_cache=[L["v_cache"] for L in hl])
+        c4 = time.perf_counter()
+        t_full = ((c1 - c0) * (total_rows / n_rows) * (w.layers / max(nl, 1)) + (c2 - c1) * (w.S / zr.shape[1])
+                  + (c4 - c3) * (w.layers / max(nl, 1)))
+        cpu = {"value": round(float(oc["commit_len"].sum()) / t_full, 2), "unit": "tokens/s",
+               "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": (f"one step of input set 0: attention {n_rows}/{total_rows} (b,i,h) rows x {nl}/{w.layers} layers, "
+                          f"confidence {zr.shape[1]}/{w.S} rows per sequence, commit in full; "
+                          "sampled parts scaled to the whole step"),
+               "ms_per_step": round(t_full * 1e3, 2), "cpu_seconds_spent": round(c4 - c0, 2)}
+
+    line = {
+        "metric": "committed tokens/sec + per-step latency (ms), LLaDA-8B shape, 1 MI355X",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "layers": w.layers, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
+                   "P": w.P, "S": w.S, "C": w.C, "V": w.V, "tau": w.tau, "window": w.window,
+                   "input_sets_rotated": R, "committed_tokens_per_step": round(committed / K, 2),
+                   "launch": "hip_graph" if graph is not None else "eager",
+                   "event_ms_per_step": round(ev0.elapsed_time(ev1) / K, 5)},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

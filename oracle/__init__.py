@@ -26,6 +26,10 @@ def lib():
     return _lib
 
 
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
 def _dt(t: torch.Tensor) -> int:
     if t.dtype == torch.float32:
         return 0

@@ -239,3 +239,11 @@ int oracle_commit(int kv_dtype, int B, int S, int V, int Hkv, int D, int C, int 
     }
     return 0;
 }
+
+/* Threads the OpenMP loops above will use (reported next to oracle timings). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif

@@ -9,17 +9,21 @@
 //   - top-2 tracking costs two operations per element: m2 = med3(m1, x, m2),
 //     m1 = max(m1, x) (valid because m2 <= m1 always);
 //   - the arg-max index is not tracked per element.  A lane only remembers in
-//     which 16-byte vector its running maximum last rose strictly; since a lane
-//     visits its elements in increasing index order, that vector holds the
-//     lane's first occurrence of its maximum, and it is re-read once at the end;
+//     which group of its 16-byte vectors its running maximum last rose
+//     strictly; since a lane visits its elements in increasing index order,
+//     that group holds the lane's first occurrence of its maximum, and it is
+//     re-read once at the end;
 //   - the soft-max sum uses one exp2 per element against a lagging per-lane
 //     reference r (log2 domain) which is only moved when the lane maximum has
-//     run more than 32 octaves ahead of it, so the rescale branch is cold.
-// Lane results are merged with an associative (max1, idx, max2, sum@ref)
-// operator in which the lower index wins on equal maxima, first across the
-// wave by shuffles, then across waves through LDS, and - when one row is split
-// over several workgroups because there are too few rows to fill the chip -
-// across workgroups by a second tiny kernel.
+//     run more than 32 octaves ahead of it, so the rescale branch is cold.  A
+//     group's top-2 pass runs before its sum pass, so the reference always
+//     covers the values being exponentiated.
+// Lane results are merged in two steps: the maximum first (DPP reduction), then
+// each lane rescales its sum to it and the runner-up, the sum and the lowest
+// index among the lanes holding the maximum are plain max / add / min
+// reductions.  The same merge runs across the waves of a workgroup through
+// LDS and - when one row is split over several workgroups because there are
+// too few rows to fill the chip - across workgroups in a second tiny kernel.
 #include <float.h>
 #include <limits.h>
 
@@ -37,7 +41,7 @@ struct Top {
   float m1, m2;  // largest and second largest value seen (duplicates count)
   float s;       // sum of exp2(x*log2e - r)
   float r;       // reference exponent (log2 domain)
-  int idx;       // >= 0: element index of the first maximum; < 0: ~(start of the vector holding it)
+  int idx;       // >= 0: element index of the first maximum; < 0: ~(first element of the lane's group holding it)
 };
 
 __device__ __forceinline__ void top_init(Top &t) {
@@ -48,43 +52,49 @@ __device__ __forceinline__ void top_init(Top &t) {
   t.idx = INT_MAX;
 }
 
+// max as exactly one v_max_f32.  fmaxf() costs two here: the kernel runs in IEEE
+// mode, where the compiler first quiets a possible signalling NaN in each
+// operand; the precondition excludes NaN, so the bare instruction is enough.
+__device__ __forceinline__ float fmax_raw(float a, float b) {
+  float d;
+  asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+  return d;
+}
+
+// Top-2 update over N values; `tag` is recorded when the maximum rose strictly.
 template <int N>
-__device__ __forceinline__ void absorb(Top &t, const float (&x)[N], int tag) {
-  const float old = t.m1;
+__device__ __forceinline__ void absorb_top2(Top &t, const float (&x)[N]) {
 #pragma unroll
   for (int j = 0; j < N; ++j) {
     t.m2 = __builtin_amdgcn_fmed3f(t.m1, x[j], t.m2);
-    t.m1 = __builtin_fmaxf(t.m1, x[j]);
+    t.m1 = fmax_raw(t.m1, x[j]);
   }
-  t.idx = t.m1 > old ? tag : t.idx;
+}
+
+// Move the reference up when the maximum has run ahead of it (cold branch).
+__device__ __forceinline__ void settle_reference(Top &t) {
   const float mc = t.m1 * kLog2e;
   if (mc - t.r > kLagOctaves) {
     t.s *= __builtin_amdgcn_exp2f(t.r - mc);
     t.r = mc;
   }
+}
+
+// Soft-max sum over N values that are already covered by t.m1 / t.r.
+template <int N>
+__device__ __forceinline__ void absorb_sum(Top &t, const float (&x)[N]) {
   const float nr = -t.r;
 #pragma unroll
   for (int j = 0; j < N; ++j) t.s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[j], kLog2e, nr));
 }
 
-__device__ __forceinline__ Top merge(const Top &a, const Top &b) {
-  Top o;
-  o.m1 = __builtin_fmaxf(a.m1, b.m1);
-  o.idx = a.m1 > b.m1 ? a.idx : (b.m1 > a.m1 ? b.idx : (a.idx < b.idx ? a.idx : b.idx));
-  o.m2 = __builtin_fmaxf(__builtin_fminf(a.m1, b.m1), __builtin_fmaxf(a.m2, b.m2));
-  o.r = __builtin_fmaxf(a.r, b.r);
-  o.s = a.s * __builtin_amdgcn_exp2f(a.r - o.r) + b.s * __builtin_amdgcn_exp2f(b.r - o.r);
-  return o;
-}
-
-__device__ __forceinline__ Top shfl_xor(const Top &t, int mask) {
-  Top o;
-  o.m1 = __shfl_xor(t.m1, mask);
-  o.m2 = __shfl_xor(t.m2, mask);
-  o.s = __shfl_xor(t.s, mask);
-  o.r = __shfl_xor(t.r, mask);
-  o.idx = __shfl_xor(t.idx, mask);
-  return o;
+template <int N>
+__device__ __forceinline__ void absorb(Top &t, const float (&x)[N], int tag) {
+  const float old = t.m1;
+  absorb_top2<N>(t, x);
+  t.idx = t.m1 > old ? tag : t.idx;
+  settle_reference(t);
+  absorb_sum<N>(t, x);
 }
 
 template <typename T>
@@ -117,8 +127,56 @@ struct Partial {  // one row segment, normalised: s = sum exp(x - m1) over the s
   int idx;
 };
 
-// One workgroup reduces elements [c0, c1) of one row.  NT threads, U vectors
-// per lane in flight per buffer, two buffers.
+// ---- cross-lane reductions on the DPP network (no LDS traffic) ---------------
+// Classic GCN reduction: two quad permutes, row shifts by 4 and 8, then the row
+// broadcasts 15 and 31; lane 63 ends up holding the reduction of all 64 lanes.
+// Lanes without a source keep op(v, v), which never feeds lane 63.
+template <typename Op>
+__device__ __forceinline__ float wave_reduce(float v, Op op) {
+#define LSP_DPP_STEP(ctrl)                                                                    \
+  v = op(v, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), \
+                                                       ctrl, 0xf, 0xf, false)))
+  LSP_DPP_STEP(0xb1);   // quad_perm [1,0,3,2]
+  LSP_DPP_STEP(0x4e);   // quad_perm [2,3,0,1]
+  LSP_DPP_STEP(0x114);  // row_shr:4
+  LSP_DPP_STEP(0x118);  // row_shr:8
+  LSP_DPP_STEP(0x142);  // row_bcast:15
+  LSP_DPP_STEP(0x143);  // row_bcast:31
+#undef LSP_DPP_STEP
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmax_raw(a, b); } };
+struct OpAdd { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
+// min over non-negative ints: their float bit patterns order the same way
+struct OpMinI {
+  __device__ __forceinline__ float operator()(float a, float b) const {
+    return __int_as_float(min(__float_as_int(a), __float_as_int(b)));
+  }
+};
+
+struct RowStat {  // wave-uniform: maximum, second, sum of exp(x - m1), first index of the maximum
+  float m1, m2, s;
+  int idx;
+};
+
+// Combine the 64 lane states of a wave.  The maximum goes first; every lane then
+// rescales its own sum to it, so the remaining reductions are plain max/add/min.
+__device__ __forceinline__ RowStat wave_combine(const Top &t) {
+  RowStat o;
+  o.m1 = wave_reduce(t.m1, OpMax());
+  const bool top = t.m1 == o.m1;
+  const int ntop = __popcll(__ballot(top));
+  const float second = wave_reduce(top ? t.m2 : t.m1, OpMax());
+  o.m2 = ntop >= 2 ? o.m1 : second;  // the maximum held by two lanes is its own runner-up
+  o.idx = __float_as_int(wave_reduce(__int_as_float(top ? t.idx : INT_MAX), OpMinI()));
+  const float w = __builtin_amdgcn_exp2f(t.r - o.m1 * kLog2e);  // 0 for an empty lane (r = -FLT_MAX)
+  const float sum = wave_reduce(t.s * w, OpAdd());
+  o.s = o.m1 == -INFINITY ? 0.f : sum;  // an all -inf segment has an empty sum
+  return o;
+}
+
+// One workgroup reduces elements [c0, c1) of one row.  NT threads; U vectors per
+// lane per group; two groups of loads in flight (ping-pong register buffers).
 template <typename T, int NT, int U>
 __global__ __launch_bounds__(NT) void confidence_kernel(
     const T *__restrict__ logits, int S, int V, int64_t row_stride, int64_t batch_stride,
@@ -152,74 +210,101 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
   const int vbase = c0 + head;  // element index of vector 0
   constexpr int G = NT * U;     // vectors per full group
   const int ngroups = nvec / G;
-  if (ngroups > 0) {
-    u32x4 cur[U], nxt[U];
+
+  auto load_group = [&](u32x4 (&buf)[U], int g) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) cur[u] = __builtin_nontemporal_load(vp + u * NT + tid);
-    for (int g = 0; g < ngroups; ++g) {
-      const int v0 = g * G + tid;
-      if (g + 1 < ngroups) {
+    for (int u = 0; u < U; ++u) buf[u] = __builtin_nontemporal_load(vp + g * G + u * NT + tid);
+  };
+  // phase 1: top-2 over the whole group, one index tag and one reference check per
+  // group; phase 2: the soft-max sum.  (The tag names the lane's first vector of the
+  // group; the lane's U vectors of that group are re-read at the end.)
+  auto process_group = [&](const u32x4 (&buf)[U], int g) {
+    float x[U][N];
+    const float old = t.m1;
 #pragma unroll
-        for (int u = 0; u < U; ++u) nxt[u] = __builtin_nontemporal_load(vp + v0 + G + u * NT);
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        float x[N];
-        Vec<T>::unpack(cur[u], x);
-        absorb<N>(t, x, ~(vbase + (v0 + u * NT) * N));
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+    for (int u = 0; u < U; ++u) {
+      Vec<T>::unpack(buf[u], x[u]);
+      absorb_top2<N>(t, x[u]);
     }
+    t.idx = t.m1 > old ? ~(vbase + (g * G + tid) * N) : t.idx;
+    settle_reference(t);
+#pragma unroll
+    for (int u = 0; u < U; ++u) absorb_sum<N>(t, x[u]);
+  };
+  if (ngroups > 0) {
+    u32x4 ping[U], pong[U];
+    load_group(ping, 0);
+    int g = 0;
+    for (; g + 1 < ngroups; g += 2) {
+      load_group(pong, g + 1);
+      process_group(ping, g);
+      if (g + 2 < ngroups) load_group(ping, g + 2);
+      process_group(pong, g + 1);
+    }
+    if (g < ngroups) process_group(ping, g);
   }
   for (int v = ngroups * G + tid; v < nvec; v += NT) {
     const u32x4 w = __builtin_nontemporal_load(vp + v);
     float x[N];
     Vec<T>::unpack(w, x);
-    absorb<N>(t, x, ~(vbase + v * N));
+    const float old = t.m1;
+    absorb_top2<N>(t, x);
+    if (t.m1 > old) {  // resolve at once: these vectors are few
+      int j = N - 1;
+#pragma unroll
+      for (int k = N - 2; k >= 0; --k) j = (x[k] == t.m1) ? k : j;
+      t.idx = vbase + v * N + j;
+    }
+    settle_reference(t);
+    absorb_sum<N>(t, x);
   }
   if (tid < c1 - tail0) {
     float x[1] = {Vec<T>::scalar(row + tail0 + tid)};
     absorb<1>(t, x, tail0 + tid);
   }
 
-  // resolve the lane's arg-max inside its remembered vector
+  // resolve the lane's arg-max inside its remembered group: scan the lane's U
+  // vectors of that group from the last to the first so the lowest index wins
   if (t.idx < 0) {
     const int e0 = ~t.idx;
-    const u32x4 w = *reinterpret_cast<const u32x4 *>(row + e0);
-    float x[N];
-    Vec<T>::unpack(w, x);
-    int j = N - 1;
+    int found = INT_MAX;
 #pragma unroll
-    for (int k = N - 2; k >= 0; --k) j = (x[k] == t.m1) ? k : j;
-    t.idx = e0 + j;
+    for (int u = U - 1; u >= 0; --u) {
+      const int eb = e0 + u * NT * N;
+      const u32x4 w = *reinterpret_cast<const u32x4 *>(row + eb);
+      float x[N];
+      Vec<T>::unpack(w, x);
+#pragma unroll
+      for (int k = N - 1; k >= 0; --k) found = (x[k] == t.m1) ? eb + k : found;
+    }
+    t.idx = found;
   }
 
-#pragma unroll
-  for (int m = 1; m < kWave; m <<= 1) t = merge(t, shfl_xor(t, m));
-
+  RowStat r = wave_combine(t);
   constexpr int NW = NT / kWave;
-  __shared__ Top lds[NW];
-  const int lane = tid & (kWave - 1), wave = tid / kWave;
   if (NW > 1) {
-    if (lane == 0) lds[wave] = t;
+    __shared__ RowStat lds[NW];
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    if (lane == 0) lds[wave] = r;
     __syncthreads();
     if (wave != 0) return;
-    if (lane < NW) t = lds[lane]; else top_init(t);
-#pragma unroll
-    for (int m = 1; m < NW; m <<= 1) t = merge(t, shfl_xor(t, m));
+    top_init(t);
+    if (lane < NW) {
+      const RowStat w = lds[lane];
+      t.m1 = w.m1; t.m2 = w.m2; t.s = w.s; t.idx = w.idx;
+      t.r = w.m1 == -INFINITY ? -FLT_MAX : w.m1 * kLog2e;
+    }
+    r = wave_combine(t);
   }
   if (tid != 0) return;
-  // an all -inf segment has an empty sum
-  const float s = t.m1 == -INFINITY ? 0.f : t.s * __builtin_amdgcn_exp2f(t.r - t.m1 * kLog2e);
   const int64_t o = int64_t(b) * S + i;
   if (splits == 1) {
-    top1_id[o] = t.idx;
-    margin[o] = t.m1 - t.m2;
-    top1_prob[o] = 1.0f / s;
+    top1_id[o] = r.idx;
+    margin[o] = r.m1 - r.m2;
+    top1_prob[o] = 1.0f / r.s;
   } else {
     Partial p;
-    p.m1 = t.m1; p.m2 = t.m2; p.s = s; p.idx = t.idx;
+    p.m1 = r.m1; p.m2 = r.m2; p.s = r.s; p.idx = r.idx;
     partials[o * splits + split] = p;
   }
 }
@@ -249,25 +334,52 @@ __global__ void confidence_finish_kernel(const Partial *__restrict__ partials, i
   top1_prob[o] = 1.0f / a.s;
 }
 
-// Rows are split only when there are too few of them to occupy the chip.
+// Launch shape.  One wave per row streams best once there are thousands of rows
+// (no barrier, finest-grained scheduling); with fewer rows the workgroup widens
+// so that about 2048 waves are in flight, and below that rows are also cut
+// into segments reduced by separate workgroups.
 struct Plan {
-  int splits, seg_elems;
+  int nt, splits, seg_elems;
 };
 inline Plan plan(int64_t rows, int V) {
   Plan p;
+  int nt = 64;
+  while (nt < 512 && rows * (nt / 64) < 2048) nt *= 2;
   int splits = 1;
-  if (rows < 192) {
-    splits = int((512 + rows - 1) / rows);
-    const int max_by_len = (V + 8191) / 8192;  // keep segments >= 8192 elements
+  const int64_t waves = rows * (nt / 64);
+  if (waves < 1024) {
+    splits = int((2048 + waves - 1) / waves);
+    const int max_by_len = (V + 16383) / 16384;  // keep segments >= 16384 elements
     if (splits > max_by_len) splits = max_by_len;
     if (splits > 32) splits = 32;
     if (splits < 1) splits = 1;
   }
   int seg = (V + splits - 1) / splits;
   seg = (seg + 63) / 64 * 64;
+  p.nt = nt;
   p.seg_elems = seg;
   p.splits = (V + seg - 1) / seg;
   return p;
+}
+
+template <typename T>
+void launch_confidence(const Plan &p, dim3 grid, hipStream_t st, const T *z, int S, int V,
+                       int64_t row_stride, int64_t batch_stride, const int32_t *suffix_len,
+                       int32_t *top1_id, float *top1_prob, float *margin, Partial *parts) {
+  switch (p.nt) {
+    case 64:
+      confidence_kernel<T, 64, 2><<<grid, 64, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
+      break;
+    case 128:
+      confidence_kernel<T, 128, 2><<<grid, 128, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
+      break;
+    case 256:
+      confidence_kernel<T, 256, 2><<<grid, 256, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
+      break;
+    default:
+      confidence_kernel<T, 512, 2><<<grid, 512, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
+      break;
+  }
 }
 
 }  // namespace
@@ -304,21 +416,12 @@ extern "C" int32_t lsp_confidence(int32_t dtype, const void *logits, int32_t B, 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const dim3 grid(p.splits, S, B);
   Partial *parts = static_cast<Partial *>(workspace);
-  const int64_t seg_bytes = int64_t(p.seg_elems) * es;
-  // big segments: 1024 threads, 4 vectors in flight per lane per buffer; small ones: 256 threads
-  if (dtype == LSP_BF16) {
-    const uint16_t *z = static_cast<const uint16_t *>(logits);
-    if (seg_bytes >= 128 * 1024)
-      confidence_kernel<uint16_t, 1024, 4><<<grid, 1024, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
-    else
-      confidence_kernel<uint16_t, 256, 4><<<grid, 256, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
-  } else {
-    const float *z = static_cast<const float *>(logits);
-    if (seg_bytes >= 128 * 1024)
-      confidence_kernel<float, 1024, 4><<<grid, 1024, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
-    else
-      confidence_kernel<float, 256, 4><<<grid, 256, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
-  }
+  if (dtype == LSP_BF16)
+    launch_confidence<uint16_t>(p, grid, st, static_cast<const uint16_t *>(logits), S, V, row_stride,
+                                batch_stride, suffix_len, top1_id, top1_prob, margin, parts);
+  else
+    launch_confidence<float>(p, grid, st, static_cast<const float *>(logits), S, V, row_stride,
+                             batch_stride, suffix_len, top1_id, top1_prob, margin, parts);
   LSP_CHECK_LAUNCH("lsp_confidence: launch");
   if (p.splits > 1) {
     const int rows = B * S;
