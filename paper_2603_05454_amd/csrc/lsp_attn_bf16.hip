@@ -23,10 +23,16 @@
 // probabilities are then at most 2^8, which bf16 and the fp32 sums hold
 // without loss, and the final division by the row sum removes the offset.
 //
-// A workgroup is WM x WK waves: WM blocks of 32 queries, and WK-way split of
-// the key range between waves of the same query block (merged through LDS at
-// the end).  Few active rows => small WM, large WK, so that short suffixes
-// still fill 256 compute units.
+// Two kernels share that arithmetic:
+//  * attn_bf16_kernel (short suffixes): a workgroup is WM x WK waves, WM blocks
+//    of 32 queries and a WK-way split of the key range between waves of the
+//    same query block (merged through LDS at the end).  Every wave streams its
+//    own K/V blocks and never waits for another wave, so a step with few
+//    active rows still fills 256 compute units and runs at memory latency.
+//  * attn_bf16_tile_kernel (long suffixes): the WM waves of a workgroup share
+//    each K/V block through a two-stage LDS ring (every wave fetches 1/WM of
+//    the block), one barrier per block; L1/L2 traffic per flop drops WM-fold,
+//    which is what the matrix cores need once the problem is compute bound.
 #include "lsp_attn.h"
 
 namespace lsp {
@@ -75,6 +81,167 @@ struct Geo {
   static constexpr int WAVE_LDS = VBYTES > OBYTES ? VBYTES : OBYTES;
 };
 
+// Second half of a 32-key block, shared by both kernels: soft-max of the score
+// block s (keys key0.., this wave's 32 queries) against the lagging reference,
+// then O^T += V^T . P^T with V read from an LDS tile of 32 rows (pitch VPITCH).
+template <int D>
+__device__ __forceinline__ void softmax_pv(f32x16 &s, f32x16 (&oacc)[D / 32], float &mref, float &lsum,
+                                           int key0, int T, float sc, int lane,
+                                           const unsigned char *vtile) {
+  constexpr int DB = D / 32;
+  constexpr int VPITCH = Geo<D>::VPITCH;
+  const int hf = lane >> 5;
+  if (key0 + 32 > T) {  // ragged last block: keys >= T get -inf
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = key0 + 8 * (r >> 2) + 4 * hf + (r & 3);
+      s[r] = key < T ? s[r] : -INFINITY;
+    }
+  }
+  float bm = fmax_raw(s[0], s[1]);
+#pragma unroll
+  for (int r = 2; r < 16; r += 2) bm = fmax3_raw(bm, s[r], s[r + 1]);
+  bm = fmax_raw(bm, other_half(bm)) * sc;  // finite: key0 < T is a valid key
+  if (__any(bm > mref + kLagOctaves)) {
+    const float mn = bm > mref + kLagOctaves ? bm : mref;
+    const float alpha = __builtin_amdgcn_exp2f(mref - mn);  // 0 on the first block (mref = -inf)
+    mref = mn;
+    lsum *= alpha;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+  }
+  const float nm = -mref;
+  bf16x8 pf[2];
+#pragma unroll
+  for (int k2 = 0; k2 < 2; ++k2) {
+    float p[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * k2 + e], sc, nm));
+      lsum += p[e];
+    }
+    u32x4 w;
+    w.x = pack_bf16(p[0], p[1]);
+    w.y = pack_bf16(p[2], p[3]);
+    w.z = pack_bf16(p[4], p[5]);
+    w.w = pack_bf16(p[6], p[7]);
+    pf[k2] = __builtin_bit_cast(bf16x8, w);
+  }
+  // O^T[d, query] += V^T[d, key] . P^T[key, query]; contraction slot 8*hf+e of
+  // step k2 is key 16*k2 + 8*(e/4) + 4*hf + e%4 (the accumulator row order).
+  // Transpose load: within 16 lanes, lane s addresses row (s/4), columns 4*(s%4)..+3
+  // and receives column s of the 4 rows.
+  const int s16 = lane & 15;
+  const unsigned char *vbase = vtile + (4 * hf + (s16 >> 2)) * VPITCH + (16 * ((lane >> 4) & 1) + 4 * (s16 & 3)) * 2;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int k2 = 0; k2 < 2; ++k2) {
+      const unsigned char *ap = vbase + (16 * k2) * VPITCH + 64 * db;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4 *)(ap));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4 *)(ap + 8 * VPITCH));
+      const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+      const u32x4 w = {l2.x, l2.y, h2.x, h2.y};
+      oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), pf[k2], oacc[db], 0, 0, 0);
+    }
+}
+
+// Workgroup placement shared by both kernels.  Workgroups are handed to the 8
+// XCDs round-robin by linear id, and each XCD has its own L2.  All workgroups
+// that read the same K/V stream - the query tiles of every query head of one
+// (sequence, KV head) unit - are therefore given ids that are congruent modulo
+// 8, so the stream is fetched into one L2 instead of eight.
+struct Place {
+  int b, g, h, q0;
+  bool valid;
+};
+__device__ __forceinline__ Place place(const AttnArgs &a, int qtile) {
+  Place p;
+  const int QT = (a.S + qtile - 1) / qtile;
+  const int rep = a.Hq / a.Hkv;
+  const int per_unit = rep * QT;
+  const int n = blockIdx.x;
+  const int m8 = n >> 3;
+  const int unit = (m8 / per_unit) * 8 + (n & 7);
+  const int wu = m8 % per_unit;
+  p.valid = unit < a.B * a.Hkv;
+  p.b = unit / a.Hkv;
+  p.g = unit % a.Hkv;
+  p.h = p.g * rep + wu / QT;
+  p.q0 = (wu % QT) * qtile;
+  return p;
+}
+
+// Final step shared by both kernels: the WK partial results of every query
+// block are combined through LDS (each wave's region holds O^T as [query][d]
+// fp32 plus m and l), normalised and stored as 16-byte bf16 chunks.
+template <int D, int WM, int WK>
+__device__ __forceinline__ void merge_store(const AttnArgs &a, const f32x16 (&oacc)[D / 32], float mref,
+                                            float lsum, unsigned char *smem, int b, int h, int q0,
+                                            int N) {
+  using G = Geo<D>;
+  constexpr int DB = D / 32;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WK, wk = wave % WK;
+  const int lq = lane & 31, hf = lane >> 5;
+  unsigned char *wlds = smem + wave * G::WAVE_LDS;
+  lsum += other_half(lsum);
+  __syncthreads();  // every wave is done with the K/V staging memory
+  float *ml = reinterpret_cast<float *>(wlds + 32 * G::OPITCH);
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const f32x4 v = {oacc[db][4 * r4], oacc[db][4 * r4 + 1], oacc[db][4 * r4 + 2], oacc[db][4 * r4 + 3]};
+      *reinterpret_cast<f32x4 *>(wlds + lq * G::OPITCH + (32 * db + 8 * r4 + 4 * hf) * 4) = v;
+    }
+  if (hf == 0) {
+    ml[lq] = mref;
+    ml[32 + lq] = lsum;
+  }
+  __syncthreads();
+  // wave (wm, wk) finishes d-range [wk*D/WK, (wk+1)*D/WK) of its query block: items = (query, 8 d)
+  constexpr int DW = D / WK;  // d columns per wave
+  constexpr int CH = DW / 8;  // 16-byte output chunks per query
+  for (int it = lane; it < 32 * CH; it += 64) {
+    const int qq = it / CH, dd = wk * DW + 8 * (it % CH);
+    const int qrow = q0 + wm * 32 + qq;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w2 = 0; w2 < WK; ++w2) {
+      const float *ml2 = reinterpret_cast<const float *>(smem + (wm * WK + w2) * G::WAVE_LDS + 32 * G::OPITCH);
+      M = fmax_raw(M, ml2[qq]);
+    }
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float den = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < WK; ++w2) {
+      const unsigned char *base = smem + (wm * WK + w2) * G::WAVE_LDS;
+      const float *ml2 = reinterpret_cast<const float *>(base + 32 * G::OPITCH);
+      const float wgt = __builtin_amdgcn_exp2f(ml2[qq] - M);  // 0 for a wave that saw no key
+      den += ml2[32 + qq] * wgt;
+      const f32x4 x0 = *reinterpret_cast<const f32x4 *>(base + qq * G::OPITCH + dd * 4);
+      const f32x4 x1 = *reinterpret_cast<const f32x4 *>(base + qq * G::OPITCH + dd * 4 + 16);
+      acc[0] += x0.x * wgt; acc[1] += x0.y * wgt; acc[2] += x0.z * wgt; acc[3] += x0.w * wgt;
+      acc[4] += x1.x * wgt; acc[5] += x1.y * wgt; acc[6] += x1.z * wgt; acc[7] += x1.w * wgt;
+    }
+    if (qrow < N) {
+      const float inv = 1.0f / den;
+      u32x4 w;
+      w.x = pack_bf16(acc[0] * inv, acc[1] * inv);
+      w.y = pack_bf16(acc[2] * inv, acc[3] * inv);
+      w.z = pack_bf16(acc[4] * inv, acc[5] * inv);
+      w.w = pack_bf16(acc[6] * inv, acc[7] * inv);
+      uint16_t *op = static_cast<uint16_t *>(a.out) + b * a.os[0] + int64_t(qrow) * a.os[1] + h * a.os[2];
+      *reinterpret_cast<u32x4 *>(op + dd) = w;
+    }
+  }
+}
+
 template <int D, int WM, int WK>
 __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) {
   using G = Geo<D>;
@@ -83,22 +250,9 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
   constexpr int VL = D / 16;  // 16-byte V loads per lane per block (32 rows * D*2 bytes / 64 lanes / 16)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-  // XCD-aware placement.  Workgroups are handed to the 8 XCDs round-robin by
-  // linear id, and each XCD has its own L2.  All workgroups that read the same
-  // K/V stream - the query tiles of every query head of one (sequence, KV head)
-  // unit - are therefore given ids that are congruent modulo 8, so the stream
-  // is fetched into one L2 instead of eight.
-  const int QT = (a.S + 32 * WM - 1) / (32 * WM);
-  const int rep = a.Hq / a.Hkv;
-  const int per_unit = rep * QT;
-  const int n = blockIdx.x;
-  const int m8 = n >> 3;
-  const int unit = (m8 / per_unit) * 8 + (n & 7);
-  if (unit >= a.B * a.Hkv) return;
-  const int wu = m8 % per_unit;
-  const int b = unit / a.Hkv, g = unit % a.Hkv;
-  const int h = g * rep + wu / QT;
-  const int q0 = (wu % QT) * (32 * WM);
+  const Place pl = place(a, 32 * WM);
+  if (!pl.valid) return;
+  const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
   const int N = min(max(a.suffix_len[b], 0), a.S);
   if (q0 >= N) return;
   const int P = min(max(a.prefix_len[b], 0), a.C);
@@ -177,63 +331,7 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
     // the K registers are free again: fetch the next block's rows while this
     // block goes through the soft-max and the second product
     if (jn < NB) load_k(jn, kf);
-    if (32 * jb + 32 > T) {  // ragged last block: keys >= T get -inf
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = 32 * jb + 8 * (r >> 2) + 4 * hf + (r & 3);
-        s[r] = key < T ? s[r] : -INFINITY;
-      }
-    }
-    float bm = fmax_raw(s[0], s[1]);
-#pragma unroll
-    for (int r = 2; r < 16; r += 2) bm = fmax3_raw(bm, s[r], s[r + 1]);
-    bm = fmax_raw(bm, other_half(bm)) * sc;  // finite: key 32*jb < T is valid
-    if (__any(bm > mref + kLagOctaves)) {
-      const float mn = bm > mref + kLagOctaves ? bm : mref;
-      const float alpha = __builtin_amdgcn_exp2f(mref - mn);  // 0 on the first block (mref = -inf)
-      mref = mn;
-      lsum *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-    }
-    const float nm = -mref;
-    bf16x8 pf[2];
-#pragma unroll
-    for (int k2 = 0; k2 < 2; ++k2) {
-      float p[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * k2 + e], sc, nm));
-        lsum += p[e];
-      }
-      u32x4 w;
-      w.x = pack_bf16(p[0], p[1]);
-      w.y = pack_bf16(p[2], p[3]);
-      w.z = pack_bf16(p[4], p[5]);
-      w.w = pack_bf16(p[6], p[7]);
-      pf[k2] = __builtin_bit_cast(bf16x8, w);
-    }
-    // O^T[d, query] += V^T[d, key] . P^T[key, query]; contraction slot 8*hf+e of
-    // step k2 is key 16*k2 + 8*(e/4) + 4*hf + e%4 (the accumulator row order).
-    // Transpose load: within 16 lanes, lane s addresses row (s/4), columns 4*(s%4)..+3
-    // and receives column s of the 4 rows.
-    const int s16 = lane & 15;
-    const unsigned char *vbase = wlds + (4 * hf + (s16 >> 2)) * G::VPITCH + (16 * ((lane >> 4) & 1) + 4 * (s16 & 3)) * 2;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2) {
-        const unsigned char *ap = vbase + (16 * k2) * G::VPITCH + 64 * db;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4 *)(ap));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4 *)(ap + 8 * G::VPITCH));
-        const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-        const u32x4 w = {l2.x, l2.y, h2.x, h2.y};
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), pf[k2], oacc[db], 0, 0, 0);
-      }
+    softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, wlds);
   };
 
   if (wk < NB) {
@@ -242,59 +340,7 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
   }
   for (int jb = wk; jb < NB; jb += WK) block(jb);
 
-  // ---- merge the WK partial results of each query block and store ----------------
-  lsum += other_half(lsum);
-  __syncthreads();  // all waves are done with their V staging area
-  float *ob = reinterpret_cast<float *>(wlds);
-  float *ml = reinterpret_cast<float *>(wlds + 32 * G::OPITCH);
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) {
-      const f32x4 v = {oacc[db][4 * r4], oacc[db][4 * r4 + 1], oacc[db][4 * r4 + 2], oacc[db][4 * r4 + 3]};
-      *reinterpret_cast<f32x4 *>(reinterpret_cast<unsigned char *>(ob) + lq * G::OPITCH + (32 * db + 8 * r4 + 4 * hf) * 4) = v;
-    }
-  if (hf == 0) {
-    ml[lq] = mref;
-    ml[32 + lq] = lsum;
-  }
-  __syncthreads();
-  // wave (wm, wk) finishes d-range [wk*D/WK, (wk+1)*D/WK) of its query block: items = (query, 8 d)
-  constexpr int DW = D / WK;            // d columns per wave
-  constexpr int CH = DW / 8;            // 16-byte output chunks per query
-  for (int it = lane; it < 32 * CH; it += 64) {
-    const int qq = it / CH, dd = wk * DW + 8 * (it % CH);
-    const int qrow = q0 + wm * 32 + qq;
-    float M = -INFINITY;
-#pragma unroll
-    for (int w2 = 0; w2 < WK; ++w2) {
-      const float *ml2 = reinterpret_cast<const float *>(smem + (wm * WK + w2) * G::WAVE_LDS + 32 * G::OPITCH);
-      M = fmax_raw(M, ml2[qq]);
-    }
-    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    float den = 0.f;
-#pragma unroll
-    for (int w2 = 0; w2 < WK; ++w2) {
-      const unsigned char *base = smem + (wm * WK + w2) * G::WAVE_LDS;
-      const float *ml2 = reinterpret_cast<const float *>(base + 32 * G::OPITCH);
-      const float wgt = __builtin_amdgcn_exp2f(ml2[qq] - M);  // 0 for a wave that saw no key
-      den += ml2[32 + qq] * wgt;
-      const f32x4 x0 = *reinterpret_cast<const f32x4 *>(base + qq * G::OPITCH + dd * 4);
-      const f32x4 x1 = *reinterpret_cast<const f32x4 *>(base + qq * G::OPITCH + dd * 4 + 16);
-      acc[0] += x0.x * wgt; acc[1] += x0.y * wgt; acc[2] += x0.z * wgt; acc[3] += x0.w * wgt;
-      acc[4] += x1.x * wgt; acc[5] += x1.y * wgt; acc[6] += x1.z * wgt; acc[7] += x1.w * wgt;
-    }
-    if (qrow < N) {
-      const float inv = 1.0f / den;
-      u32x4 w;
-      w.x = pack_bf16(acc[0] * inv, acc[1] * inv);
-      w.y = pack_bf16(acc[2] * inv, acc[3] * inv);
-      w.z = pack_bf16(acc[4] * inv, acc[5] * inv);
-      w.w = pack_bf16(acc[6] * inv, acc[7] * inv);
-      uint16_t *op = static_cast<uint16_t *>(a.out) + b * a.os[0] + int64_t(qrow) * a.os[1] + h * a.os[2];
-      *reinterpret_cast<u32x4 *>(op + dd) = w;
-    }
-  }
+  merge_store<D, WM, WK>(a, oacc, mref, lsum, smem, b, h, q0, N);
 }
 
 template <int D, int WM, int WK>
@@ -321,11 +367,168 @@ int32_t launch(const AttnArgs &a, hipStream_t st) {
   return LSP_OK;
 }
 
+// ---- long-suffix kernel: K/V blocks shared by the WM waves through LDS -----------
+template <int D>
+struct TileGeo {
+  static constexpr int KPITCH = D * 2 + 16;  // bytes per K row: 16 mod 256 keeps 16-byte column reads conflict-free
+  static constexpr int VPITCH = Geo<D>::VPITCH;
+  static constexpr int KBYTES = 32 * KPITCH;
+  static constexpr int STAGE = KBYTES + 32 * VPITCH;
+};
+
+template <int D, int WM, int OCC, int PD>
+__global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a) {
+  using TG = TileGeo<D>;
+  constexpr int NT = 64 * WM;
+  constexpr int KK = D / 16;
+  constexpr int DB = D / 32;
+  constexpr int CPR = D / 8;               // 16-byte pieces per row
+  constexpr int PIECES = 32 * CPR / NT;    // pieces of K (and of V) per thread per block
+  static_assert(32 * CPR % NT == 0, "loader mapping");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const Place pl = place(a, 32 * WM);
+  if (!pl.valid) return;
+  const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
+  const int N = min(max(a.suffix_len[b], 0), a.S);
+  if (q0 >= N) return;
+  const int P = min(max(a.prefix_len[b], 0), a.C);
+  const int T = P + N;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lq = lane & 31, hf = lane >> 5;
+
+  const uint16_t *kc = static_cast<const uint16_t *>(a.k_cache) + b * a.cs[0] + g * a.cs[2];
+  const uint16_t *vc = static_cast<const uint16_t *>(a.v_cache) + b * a.cs[0] + g * a.cs[2];
+  const uint16_t *ks = static_cast<const uint16_t *>(a.k_suf) + b * a.ks[0] + g * a.ks[2];
+  const uint16_t *vs = static_cast<const uint16_t *>(a.v_suf) + b * a.ks[0] + g * a.ks[2];
+
+  const int qi = q0 + wave * 32 + lq;
+  const uint16_t *qp = static_cast<const uint16_t *>(a.q) + b * a.qs[0] + int64_t(min(qi, N - 1)) * a.qs[1] + h * a.qs[2];
+  bf16x8 qf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8 *>(qp + 16 * kk + 8 * hf);
+
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float mref = -INFINITY, lsum = 0.f;
+  const float sc = a.scale * kLog2e;
+  const int NB = (T + 31) >> 5;
+
+  // loader: piece i of this thread is (row, 16-byte column) = ((tid + NT*i) / CPR, (tid + NT*i) % CPR).
+  // PD register sets hold the blocks in flight: the loop is throughput-bound by
+  // bytes in flight per compute unit, so the prefetch distance is a tuning knob.
+  u32x4 kreg[PD][PIECES], vreg[PD][PIECES];
+  auto load_block = [&](int jb, u32x4 (&kr)[PIECES], u32x4 (&vr)[PIECES]) {
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) {
+      const int pc = tid + NT * i;
+      const int t = min(32 * jb + pc / CPR, T - 1);
+      const int64_t off = t < P ? int64_t(t) * a.cs[1] : int64_t(t - P) * a.ks[1];
+      const uint16_t *kp = (t < P ? kc : ks) + off + 8 * (pc % CPR);
+      const uint16_t *vp = (t < P ? vc : vs) + off + 8 * (pc % CPR);
+      kr[i] = *reinterpret_cast<const u32x4 *>(kp);
+      vr[i] = *reinterpret_cast<const u32x4 *>(vp);
+    }
+  };
+  auto store_block = [&](int jb, const u32x4 (&kr)[PIECES], const u32x4 (&vr)[PIECES]) {
+    unsigned char *st = smem + (jb & 1) * TG::STAGE;
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) {
+      const int pc = tid + NT * i;
+      const int r = pc / CPR, c = pc % CPR;
+      u32x4 v = vr[i];
+      if (32 * jb + r >= T) v = u32x4{0, 0, 0, 0};  // keys beyond T contribute exact zeros
+      *reinterpret_cast<u32x4 *>(st + r * TG::KPITCH + 16 * c) = kr[i];
+      *reinterpret_cast<u32x4 *>(st + TG::KBYTES + r * TG::VPITCH + 16 * c) = v;
+    }
+  };
+
+  // prologue: block 0 goes to stage 0; register set u then holds block u+1
+  load_block(0, kreg[0], vreg[0]);
+  store_block(0, kreg[0], vreg[0]);
+#pragma unroll
+  for (int u = 0; u < PD; ++u)
+    if (u + 1 < NB) load_block(u + 1, kreg[u], vreg[u]);
+  __syncthreads();
+  for (int jb0 = 0; jb0 < NB; jb0 += PD) {
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {
+      const int jb = jb0 + u;
+      if (jb >= NB) break;
+      // block jb+1 (register set u) goes into the stage that every wave finished
+      // reading before the last barrier; the set is refilled with block jb+1+PD
+      if (jb + 1 < NB) store_block(jb + 1, kreg[u], vreg[u]);
+      if (jb + 1 + PD < NB) load_block(jb + 1 + PD, kreg[u], vreg[u]);
+      const unsigned char *st = smem + (jb & 1) * TG::STAGE;
+      f32x16 s;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + lq * TG::KPITCH + (16 * kk + 8 * hf) * 2);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+      }
+      softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, st + TG::KBYTES);
+      __syncthreads();
+    }
+  }
+  // No key split here, so a lane already owns whole outputs: normalise and store
+  // its 4-element runs directly (8 bytes each; once per workgroup, after a long
+  // key loop, so the short stores do not matter and no LDS is needed).
+  lsum += other_half(lsum);
+  if (qi < N) {
+    const float inv = 1.0f / lsum;
+    uint16_t *op = static_cast<uint16_t *>(a.out) + b * a.os[0] + int64_t(qi) * a.os[1] + h * a.os[2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        u32x2 w;
+        w.x = pack_bf16(oacc[db][4 * r4] * inv, oacc[db][4 * r4 + 1] * inv);
+        w.y = pack_bf16(oacc[db][4 * r4 + 2] * inv, oacc[db][4 * r4 + 3] * inv);
+        *reinterpret_cast<u32x2 *>(op + 32 * db + 8 * r4 + 4 * hf) = w;
+      }
+  }
+}
+
+template <int D, int WM, int OCC, int PD>
+int32_t launch_tile(const AttnArgs &a, hipStream_t st) {
+  const int64_t QT = (a.S + 32 * WM - 1) / (32 * WM);
+  const int64_t units = int64_t(a.B) * a.Hkv;
+  const int64_t nwg = (units + 7) / 8 * 8 * (a.Hq / a.Hkv) * QT;
+  if (nwg > 0x7fffffff) {
+    set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
+    return LSP_ERR_UNSUPPORTED;
+  }
+  const size_t lds = 2 * size_t(TileGeo<D>::STAGE);
+  auto kern = attn_bf16_tile_kernel<D, WM, OCC, PD>;
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+    if (e != hipSuccess) return hip_fail(e, "lsp_attn_step: hipFuncSetAttribute");
+    configured = true;
+  }
+  kern<<<dim3(static_cast<unsigned>(nwg), 1, 1), 64 * WM, lds, st>>>(a);
+  LSP_CHECK_LAUNCH("lsp_attn_step: bf16 tile launch");
+  return LSP_OK;
+}
+
 template <int D>
 int32_t dispatch(const AttnArgs &a, hipStream_t st) {
-  // Pick the widest query tile that still gives every compute unit work.
+  // Enough (sequence, head, row) triples to give every compute unit several
+  // query tiles: the shared-tile kernel, with the widest tile the suffix fills.
+  // Otherwise the wave-private kernel with the key range split between waves.
   const int64_t rows = int64_t(a.B) * a.Hq * a.S;  // upper bound on (b,h,row) triples
-  if (rows / 128 >= 512) return launch<D, 4, 1>(a, st);
+  if (rows / 128 >= 256) {
+    if constexpr (D == 128) {
+      if (a.S > 128) return launch_tile<D, 8, 2, 6>(a, st);
+    }
+    return launch_tile<D, 4, 2, 4>(a, st);
+  }
   if (rows / 64 >= 512) return launch<D, 2, 2>(a, st);
   if (rows / 32 >= 512) return launch<D, 1, 4>(a, st);
   return launch<D, 1, 8>(a, st);

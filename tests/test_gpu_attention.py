@@ -126,3 +126,32 @@ def test_c3_gqa_sampled(lsp, oracle):
 
 def test_c4_shape_one_layer_sampled(lsp, oracle):
     _sampled(lsp, oracle, W.C4, n=64, layer=5)
+
+
+@pytest.mark.parametrize("D,Hq,Hkv,S", [(128, 16, 4, 600), (64, 16, 16, 520), (128, 72, 8, 100)])
+def test_many_rows_ragged_lengths_sampled(lsp, oracle, D, Hq, Hkv, S):
+    """Enough (sequence, head, row) triples to take the long-suffix launch shape,
+    with per-sequence lengths that end inside tiles: sampled rows against the
+    oracle, every inactive row untouched."""
+    w = W.scaled(W.C2, B=5, S=S, P=300, C=384, Hq=Hq, Hkv=Hkv, D=D, seed=31 + D + S)
+    pl = torch.tensor([300, 0, 77, 131, 384], dtype=torch.int32)
+    sl = torch.tensor([S, S - 71, 0, 1, 257 if S > 257 else S - 3], dtype=torch.int32)
+    kv = W.make_layer_kv(w, 0, prefix_len=pl)
+    got = _run(lsp, kv, pl, sl)
+    g = torch.Generator().manual_seed(5)
+    rows = []
+    for b in range(w.B):
+        n = int(sl[b])
+        if n == 0:
+            continue
+        ii = torch.randint(0, n, (24,), generator=g).tolist() + [0, n - 1]
+        hh = torch.randint(0, Hq, (26,), generator=g).tolist()
+        rows += [[b, i, h] for i, h in zip(ii, hh)]
+    rows = torch.tensor(rows, dtype=torch.int32)
+    ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl, rows=rows)
+    sel = got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()]
+    err = (sel - ref).abs().max().item()
+    assert err <= 2e-2, err
+    for b in range(w.B):
+        assert torch.all(got[b, int(sl[b]):] == 123.0)
+        assert not torch.isnan(got[b, : int(sl[b])]).any()
