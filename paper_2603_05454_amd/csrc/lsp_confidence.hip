@@ -12,7 +12,8 @@
 //     which group of its 16-byte vectors its running maximum last rose
 //     strictly; since a lane visits its elements in increasing index order,
 //     that group holds the lane's first occurrence of its maximum, and it is
-//     re-read once at the end;
+//     re-read once at the end - by the lanes that hold the wave's maximum only
+//     (every lane doing so would add 16 KB of scattered cache lines per wave);
 //   - the soft-max sum uses one exp2 per element against a lagging per-lane
 //     reference r (log2 domain) which is only moved when the lane maximum has
 //     run more than 32 octaves ahead of it, so the rescale branch is cold.  A
@@ -26,6 +27,8 @@
 // too few rows to fill the chip - across workgroups in a second tiny kernel.
 #include <float.h>
 #include <limits.h>
+
+#include <type_traits>
 
 #include "lsp_common.h"
 
@@ -159,11 +162,12 @@ struct RowStat {  // wave-uniform: maximum, second, sum of exp(x - m1), first in
   int idx;
 };
 
-// Combine the 64 lane states of a wave.  The maximum goes first; every lane then
-// rescales its own sum to it, so the remaining reductions are plain max/add/min.
-__device__ __forceinline__ RowStat wave_combine(const Top &t) {
+// Combine the 64 lane states of a wave, given the maximum over the lanes.  Every
+// lane rescales its own sum to that maximum, so the remaining reductions are
+// plain max/add/min.  A lane's idx is only read when the lane holds the maximum.
+__device__ __forceinline__ RowStat wave_combine(const Top &t, float wave_max) {
   RowStat o;
-  o.m1 = wave_reduce(t.m1, OpMax());
+  o.m1 = wave_max;
   const bool top = t.m1 == o.m1;
   const int ntop = __popcll(__ballot(top));
   const float second = wave_reduce(top ? t.m2 : t.m1, OpMax());
@@ -208,22 +212,32 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
 
   const u32x4 *vp = reinterpret_cast<const u32x4 *>(row + c0 + head);
   const int vbase = c0 + head;  // element index of vector 0
-  constexpr int G = NT * U;     // vectors per full group
-  const int ngroups = nvec / G;
+  constexpr int G = NT * U;     // vectors per group
+  const int ngroups = (nvec + G - 1) / G;  // the last one may be partial
 
-  auto load_group = [&](u32x4 (&buf)[U], int g) {
+  // Lanes past the end of the last, partial group re-read the row's last vector
+  // (their values are replaced by -inf below), so that group is one burst of
+  // loads like every other.
+  auto load_group = [&](u32x4 (&buf)[U], int g, auto last) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) buf[u] = __builtin_nontemporal_load(vp + g * G + u * NT + tid);
+    for (int u = 0; u < U; ++u) {
+      const int v = g * G + u * NT + tid;
+      buf[u] = __builtin_nontemporal_load(vp + (decltype(last)::value ? min(v, nvec - 1) : v));
+    }
   };
   // phase 1: top-2 over the whole group, one index tag and one reference check per
   // group; phase 2: the soft-max sum.  (The tag names the lane's first vector of the
   // group; the lane's U vectors of that group are re-read at the end.)
-  auto process_group = [&](const u32x4 (&buf)[U], int g) {
+  auto process_group = [&](const u32x4 (&buf)[U], int g, auto last) {
     float x[U][N];
     const float old = t.m1;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       Vec<T>::unpack(buf[u], x[u]);
+      if (decltype(last)::value && g * G + u * NT + tid >= nvec) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) x[u][k] = -INFINITY;  // never the maximum, adds 0 to the sum
+      }
       absorb_top2<N>(t, x[u]);
     }
     t.idx = t.m1 > old ? ~(vbase + (g * G + tid) * N) : t.idx;
@@ -232,45 +246,48 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
     for (int u = 0; u < U; ++u) absorb_sum<N>(t, x[u]);
   };
   if (ngroups > 0) {
+    const std::false_type full;
+    const std::true_type maybe_partial;
     u32x4 ping[U], pong[U];
-    load_group(ping, 0);
+    if (ngroups == 1) load_group(ping, 0, maybe_partial); else load_group(ping, 0, full);
     int g = 0;
-    for (; g + 1 < ngroups; g += 2) {
-      load_group(pong, g + 1);
-      process_group(ping, g);
-      if (g + 2 < ngroups) load_group(ping, g + 2);
-      process_group(pong, g + 1);
+    for (; g + 3 < ngroups; g += 2) {  // groups g+1 and g+2 are full
+      load_group(pong, g + 1, full);
+      process_group(ping, g, full);
+      load_group(ping, g + 2, full);
+      process_group(pong, g + 1, full);
     }
-    if (g < ngroups) process_group(ping, g);
-  }
-  for (int v = ngroups * G + tid; v < nvec; v += NT) {
-    const u32x4 w = __builtin_nontemporal_load(vp + v);
-    float x[N];
-    Vec<T>::unpack(w, x);
-    const float old = t.m1;
-    absorb_top2<N>(t, x);
-    if (t.m1 > old) {  // resolve at once: these vectors are few
-      int j = N - 1;
-#pragma unroll
-      for (int k = N - 2; k >= 0; --k) j = (x[k] == t.m1) ? k : j;
-      t.idx = vbase + v * N + j;
+    // one to three groups left; only the very last may be partial
+    if (g + 2 < ngroups) {
+      load_group(pong, g + 1, full);
+      process_group(ping, g, full);
+      load_group(ping, g + 2, maybe_partial);
+      process_group(pong, g + 1, full);
+      process_group(ping, g + 2, maybe_partial);
+    } else if (g + 1 < ngroups) {
+      load_group(pong, g + 1, maybe_partial);
+      process_group(ping, g, full);
+      process_group(pong, g + 1, maybe_partial);
+    } else {
+      process_group(ping, g, maybe_partial);
     }
-    settle_reference(t);
-    absorb_sum<N>(t, x);
   }
   if (tid < c1 - tail0) {
     float x[1] = {Vec<T>::scalar(row + tail0 + tid)};
     absorb<1>(t, x, tail0 + tid);
   }
 
-  // resolve the lane's arg-max inside its remembered group: scan the lane's U
-  // vectors of that group from the last to the first so the lowest index wins
-  if (t.idx < 0) {
+  // Only a lane that holds the wave's maximum can own the arg-max, so only such
+  // a lane (usually one) re-reads its remembered group: its U vectors of that
+  // group, scanned from the last to the first so that the lowest index wins.
+  const float wave_max = wave_reduce(t.m1, OpMax());
+  if (t.idx < 0 && t.m1 == wave_max) {
     const int e0 = ~t.idx;
     int found = INT_MAX;
 #pragma unroll
     for (int u = U - 1; u >= 0; --u) {
       const int eb = e0 + u * NT * N;
+      if (eb >= tail0) continue;  // past the end of a partial group
       const u32x4 w = *reinterpret_cast<const u32x4 *>(row + eb);
       float x[N];
       Vec<T>::unpack(w, x);
@@ -280,7 +297,7 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
     t.idx = found;
   }
 
-  RowStat r = wave_combine(t);
+  RowStat r = wave_combine(t, wave_max);
   constexpr int NW = NT / kWave;
   if (NW > 1) {
     __shared__ RowStat lds[NW];
@@ -294,7 +311,7 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
       t.m1 = w.m1; t.m2 = w.m2; t.s = w.s; t.idx = w.idx;
       t.r = w.m1 == -INFINITY ? -FLT_MAX : w.m1 * kLog2e;
     }
-    r = wave_combine(t);
+    r = wave_combine(t, wave_reduce(t.m1, OpMax()));
   }
   if (tid != 0) return;
   const int64_t o = int64_t(b) * S + i;
@@ -334,10 +351,13 @@ __global__ void confidence_finish_kernel(const Partial *__restrict__ partials, i
   top1_prob[o] = 1.0f / a.s;
 }
 
-// Launch shape.  One wave per row streams best once there are thousands of rows
-// (no barrier, finest-grained scheduling); with fewer rows the workgroup widens
-// so that about 2048 waves are in flight, and below that rows are also cut
-// into segments reduced by separate workgroups.
+// Launch shape (measured on MI355X).  One wave per row streams best once there
+// are thousands of rows (no barrier, finest-grained scheduling); with fewer
+// rows the workgroup widens so that about 2048 waves are in flight, and below
+// that rows are also cut into segments reduced by separate workgroups.  More
+// waves or more vectors per lane than this did not help: per element the
+// kernel issues about nine VALU cycles (the exponential counts four), which at
+// these sizes is as long as the memory time itself.
 struct Plan {
   int nt, splits, seg_elems;
 };
@@ -362,24 +382,28 @@ inline Plan plan(int64_t rows, int V) {
   return p;
 }
 
+template <typename T, int NT, int U>
+void launch_one(const Plan &p, dim3 grid, hipStream_t st, const T *z, int S, int V,
+                int64_t row_stride, int64_t batch_stride, const int32_t *suffix_len,
+                int32_t *top1_id, float *top1_prob, float *margin, Partial *parts) {
+  confidence_kernel<T, NT, U><<<grid, NT, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len,
+                                                   p.splits, p.seg_elems, top1_id, top1_prob,
+                                                   margin, parts);
+}
+
 template <typename T>
 void launch_confidence(const Plan &p, dim3 grid, hipStream_t st, const T *z, int S, int V,
                        int64_t row_stride, int64_t batch_stride, const int32_t *suffix_len,
                        int32_t *top1_id, float *top1_prob, float *margin, Partial *parts) {
-  switch (p.nt) {
-    case 64:
-      confidence_kernel<T, 64, 2><<<grid, 64, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
-      break;
-    case 128:
-      confidence_kernel<T, 128, 2><<<grid, 128, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
-      break;
-    case 256:
-      confidence_kernel<T, 256, 2><<<grid, 256, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
-      break;
-    default:
-      confidence_kernel<T, 512, 2><<<grid, 512, 0, st>>>(z, S, V, row_stride, batch_stride, suffix_len, p.splits, p.seg_elems, top1_id, top1_prob, margin, parts);
-      break;
-  }
+#define LSP_CONF_CASE(NT_)                                                                      \
+  if (p.nt == NT_)                                                                              \
+    return launch_one<T, NT_, 2>(p, grid, st, z, S, V, row_stride, batch_stride, suffix_len,    \
+                                 top1_id, top1_prob, margin, parts)
+  LSP_CONF_CASE(64);
+  LSP_CONF_CASE(128);
+  LSP_CONF_CASE(256);
+  LSP_CONF_CASE(512);
+#undef LSP_CONF_CASE
 }
 
 }  // namespace
