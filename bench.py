@@ -27,9 +27,19 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 MALL_BYTES = 256 << 20
 
-# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (summaries under profiles/); None where no counter run has been made.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (one counter per run,
+# FETCH scaled x2 KiB and WRITE x1 KiB by the 1 GiB copy calibration; summary under profiles/):
+# (workload, call) -> read + written bytes.  None where no counter run has been made.
+_KIB = 1024
+MEASURED_TRAFFIC = {
+    ("c2", "lsp_confidence"): (31812.4 * 2 + 24.0) * _KIB,
+    ("c2", "lsp_attn_step"): (7234.6 * 2 + 2048.0) * _KIB,
+    ("c2", "lsp_commit"): ((916.5 + 4.3) * 2 + 1796.0 + 0.9) * _KIB,
+    ("c3", "lsp_confidence"): (304446.7 * 2 + 192.0) * _KIB,
+    ("c3", "lsp_attn_step"): (13435.5 * 2 + 14382.4) * _KIB,
+    ("c4", "lsp_confidence"): (1012834.8 * 2 + 775.1) * _KIB,
+    ("c4", "lsp_attn_step"): (360580.7 * 2 + 65583.3) * _KIB,
+}
 
 
 def parse():
@@ -187,7 +197,7 @@ def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True):
     kd = kernels[dom]
     roofline = {"kernel": dom, "bound": kd["bound"], "achieved": round(kd["achieved"], 2), "peak": kd["peak"],
                 "unit": kd["unit"], "frac": round(kd["achieved"] / kd["peak"], 4),
-                "traffic": MEASURED_TRAFFIC.get((name, dom)),
+                "traffic": MEASURED_TRAFFIC.get((name, dom)), "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, profiles/)",
                 "avg_launch_us": round(kd["s"] * 1e6, 2),
                 "all": {k: {"avg_us": round(v["s"] * 1e6, 2), "achieved": round(v["achieved"], 2), "unit": v["unit"],
                             "frac": round(v["achieved"] / v["peak"], 4)} for k, v in kernels.items()}}
