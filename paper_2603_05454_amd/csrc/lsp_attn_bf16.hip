@@ -69,8 +69,18 @@ __device__ __forceinline__ float fmax3_raw(float a, float b, float c) {
   return d;
 }
 
-// value held by the lane 32 away
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }
+// Reductions over the two lanes l and l+32 (the two halves of an accumulator
+// column), result in both lanes.  v_permlane32_swap with both operands equal
+// hands every lane the lower-half value and the upper-half value of its column
+// as a register pair: one VALU instruction instead of a trip through LDS.
+__device__ __forceinline__ float half_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmax_raw(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 template <int D>
 struct Geo {
@@ -101,7 +111,7 @@ __device__ __forceinline__ void softmax_pv(f32x16 &s, f32x16 (&oacc)[D / 32], fl
   float bm = fmax_raw(s[0], s[1]);
 #pragma unroll
   for (int r = 2; r < 16; r += 2) bm = fmax3_raw(bm, s[r], s[r + 1]);
-  bm = fmax_raw(bm, other_half(bm)) * sc;  // finite: key0 < T is a valid key
+  bm = half_max(bm) * sc;  // finite: key0 < T is a valid key
   if (__any(bm > mref + kLagOctaves)) {
     const float mn = bm > mref + kLagOctaves ? bm : mref;
     const float alpha = __builtin_amdgcn_exp2f(mref - mn);  // 0 on the first block (mref = -inf)
@@ -189,7 +199,7 @@ __device__ __forceinline__ void merge_store(const AttnArgs &a, const f32x16 (&oa
   const int wm = wave / WK, wk = wave % WK;
   const int lq = lane & 31, hf = lane >> 5;
   unsigned char *wlds = smem + wave * G::WAVE_LDS;
-  lsum += other_half(lsum);
+  lsum = half_sum(lsum);
   __syncthreads();  // every wave is done with the K/V staging memory
   float *ml = reinterpret_cast<float *>(wlds + 32 * G::OPITCH);
 #pragma unroll
@@ -478,7 +488,7 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
   // No key split here, so a lane already owns whole outputs: normalise and store
   // its 4-element runs directly (8 bytes each; once per workgroup, after a long
   // key loop, so the short stores do not matter and no LDS is needed).
-  lsum += other_half(lsum);
+  lsum = half_sum(lsum);
   if (qi < N) {
     const float inv = 1.0f / lsum;
     uint16_t *op = static_cast<uint16_t *>(a.out) + b * a.os[0] + int64_t(qi) * a.os[1] + h * a.os[2];
