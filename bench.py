@@ -52,11 +52,14 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also", default="c3,c4", help="comma list of further workloads timed briefly (\"\" = none)")
     ap.add_argument("--calibrate-copy", action="store_true", help="only run the 1 GiB copy used to scale HBM counters")
+    ap.add_argument("--overlap", type=int, default=0,
+                    help="1: run lsp_attn_step on a second stream beside lsp_confidence (measured: the two "
+                         "cross-stream joins per step cost more than the overlap gains at c2, and gain <1%% at c4)")
     ap.add_argument("--graph", type=int, default=1, help="replay the step from a HIP graph (1) or launch eagerly (0)")
     return ap.parse_args()
 
 
-def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True):
+def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True, overlap=False):
     """Time K steps of one workload; returns (value, ms_per_step, config, roofline, cpu_baseline)."""
     import torch
     import paper_2603_05454_amd as lsp
@@ -99,11 +102,13 @@ def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True):
     ws_bytes = max(lsp.confidence_workspace_bytes(w.B, w.S, w.V),
                    lsp.attn_workspace_bytes(lsp.LSP_BF16 if w.dtype == "bf16" else lsp.LSP_F32, w.B, w.S, w.Hq, w.Hkv, w.D, w.C), 256)
     workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    workspace_attn = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)   # the two calls may run side by side
+    side = torch.cuda.Stream() if overlap else None                        # default priority
 
     def attn(s, pl, sl):
         for L in s["layers"]:
             lsp.attn_step(L["q"], L["k_suf"], L["v_suf"], L["k_cache"], L["v_cache"], pl, sl,
-                          out=s["attn_out"], workspace=workspace)
+                          out=s["attn_out"], workspace=workspace_attn)
 
     def conf(s, sl):
         lsp.confidence(s["z"], sl, out=conf_out, workspace=workspace)
@@ -114,8 +119,18 @@ def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True):
 
     def step(i):
         s = sets[i % R]
-        attn(s, PL[i], SL[i])
-        conf(s, SL[i])
+        if side is None:
+            attn(s, PL[i], SL[i])
+            conf(s, SL[i])
+        else:
+            # attention (K/V, lengths) and confidence (logits, lengths) share no data: the attention of
+            # every layer goes to a second stream and joins before the commit, which writes the caches
+            main = torch.cuda.current_stream()
+            side.wait_stream(main)
+            with torch.cuda.stream(side):
+                attn(s, PL[i], SL[i])
+            conf(s, SL[i])
+            main.wait_stream(side)
         commit(s, PL[i], SL[i], commit_out[i])
 
     # ---- whole-step timing --------------------------------------------------------
@@ -262,7 +277,7 @@ def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True):
     config = {"workload": w.name, "B": w.B, "layers": w.layers, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
               "P": w.P, "S": w.S, "C": w.C, "V": w.V, "tau": w.tau, "window": w.window,
               "input_sets_rotated": R, "committed_tokens_per_step": round(committed / K, 2),
-              "launch": "hip_graph" if graph is not None else "eager",
+              "launch": ("hip_graph" if graph is not None else "eager") + (", attention on a second stream beside confidence" if overlap else ""),
               "event_ms_per_step": round(ev0.elapsed_time(ev1) / K, 5), "dtype": w.dtype}
     return value, ms_per_step, config, roofline, cpu
 
@@ -297,13 +312,13 @@ def main():
     K, Wm = args.steps, args.warmup
     value, ms_per_step, config, roofline, cpu = run_workload(
         args.workload, K, Wm, layers=args.layers, use_graph=bool(args.graph),
-        cpu_baseline=not args.no_cpu_baseline)
+        cpu_baseline=not args.no_cpu_baseline, overlap=bool(args.overlap))
     # the same path at the larger shapes, where the kernels are bandwidth / matrix-core bound
     # rather than launch bound (fewer steps; reported next to the headline workload)
     at_scale = {}
     for extra in [e for e in args.also.split(",") if e and e != args.workload]:
         torch.cuda.empty_cache()
-        v, ms, cfg, rf, _ = run_workload(extra, 10, 5, use_graph=bool(args.graph), cpu_baseline=False)
+        v, ms, cfg, rf, _ = run_workload(extra, 10, 5, use_graph=bool(args.graph), cpu_baseline=False, overlap=bool(args.overlap))
         at_scale[cfg["workload"]] = {"value": round(v, 1), "ms_per_step": round(ms, 5), "layers": cfg["layers"],
                                      "committed_tokens_per_step": cfg["committed_tokens_per_step"],
                                      "kernels": rf["all"]}
