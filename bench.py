@@ -47,7 +47,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--loop-steps", type=int, default=0, help="c5: stop the decode loop after this many steps (0 = run to the end)")
     ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also", default="c3,c4", help="comma list of further workloads timed briefly (\"\" = none)")
@@ -282,6 +283,42 @@ def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True, overl
     return value, ms_per_step, config, roofline, cpu
 
 
+def run_loop_workload(max_steps=0):
+    """Config 5: the whole decode loop (Algorithm 1 lines 3-11) at LLaDA-8B shape, batch 16,
+    prompt 512, 1024 generated positions, all 32 layers' attention and KV append every step.
+    The step's logits come from the seeded synthetic process (workloads.make_process_logits),
+    which stands in for the denoiser and is NOT part of the timed path: every step's library
+    calls are bracketed by HIP events and the sum is the loop time."""
+    import torch
+    import paper_2603_05454_amd as lsp
+    from paper_2603_05454_amd.loop import decode_loop
+    import workloads as W
+
+    dev = torch.device("cuda:0")
+    w = W.C5
+    _, bitmap = W.make_delimiters(w)
+    layers = [W.make_layer_kv(w, l, device=dev) for l in range(w.layers)]
+    pl, sl = W.make_lengths(w, device=dev)
+    tokens = W.make_tokens(w, w.C).to(dev)
+    fn = lambda step, p: W.make_process_logits(w, dev, step, p)[0]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    r = decode_loop(fn, bitmap.to(dev), w.V, w.tau, w.window, w.min_commit, 1, pl, sl, tokens,
+                    kv_layers=layers, gen_len=w.gen_len, run_attention=True, timed=True,
+                    stop_after=max_steps or None)
+    wall = time.perf_counter() - t0
+    lsp_s = r["lsp_ms"] * 1e-3
+    config = {"workload": w.name, "B": w.B, "layers": w.layers, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
+              "P": w.P, "gen_len": w.gen_len, "C": w.C, "V": w.V, "tau": w.tau, "window": w.window,
+              "loop_steps": r["steps"], "committed_tokens": r["committed"], "flips": r["flips"],
+              "flip_rate": round(r["flips"] / max(1, r["flip_denominator"]), 5),
+              "ms_at_steps": {str(i): round(r["lsp_ms_steps"][i], 3)
+                              for i in sorted({0, 1, r["steps"] // 4, r["steps"] // 2, 3 * r["steps"] // 4, r["steps"] - 1})},
+              "lsp_seconds": round(lsp_s, 4), "wall_seconds_with_logit_generator": round(wall, 2),
+              "launch": "eager, one termination poll per step", "dtype": w.dtype}
+    return r["committed"] / lsp_s, r["lsp_ms"] / max(1, r["steps"]), config
+
+
 def calibrate_copy():
     """A plain device-to-device copy of known size (1 GiB read + 1 GiB written per
     launch, 5 launches): what rocprofv3's FETCH_SIZE / WRITE_SIZE counters read
@@ -310,6 +347,14 @@ def main():
         calibrate_copy()
         return
     K, Wm = args.steps, args.warmup
+    if args.workload == "c5":
+        value, ms, config = run_loop_workload(args.loop_steps)
+        print(json.dumps({"metric": "committed tokens/sec + per-step latency (ms), LLaDA-8B shape, 1 MI355X",
+                          "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": config["loop_steps"],
+                          "warmup": 0, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+                          "vs_baseline": None, "dtype": config.pop("dtype"), "data": "synthetic", "config": config,
+                          "roofline": None, "cpu_baseline": None}))
+        return
     value, ms_per_step, config, roofline, cpu = run_workload(
         args.workload, K, Wm, layers=args.layers, use_graph=bool(args.graph),
         cpu_baseline=not args.no_cpu_baseline, overlap=bool(args.overlap))

@@ -12,6 +12,7 @@ struct AttnArgs {
   float scale;
   int64_t qs[3], ks[3], cs[3], os[3];  // element strides: batch, row, head
   void *workspace;
+  int32_t unit_group;  // set by the bf16 launcher: units per placement group
 };
 
 int32_t launch_attn_f32(const AttnArgs &a, hipStream_t st);

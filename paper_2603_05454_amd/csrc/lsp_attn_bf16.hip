@@ -34,6 +34,9 @@
 //    the block), one barrier per block; L1/L2 traffic per flop drops WM-fold,
 //    which is what the matrix cores need once the problem is compute bound.
 #include "lsp_attn.h"
+#ifdef LSP_TUNE
+#include <stdlib.h>
+#endif
 
 namespace lsp {
 namespace {
@@ -165,6 +168,16 @@ __device__ __forceinline__ void softmax_pv(f32x16 &s, f32x16 (&oacc)[D / 32], fl
 // that read the same K/V stream - the query tiles of every query head of one
 // (sequence, KV head) unit - are therefore given ids that are congruent modulo
 // 8, so the stream is fetched into one L2 instead of eight.
+// Within an XCD the order is: groups of kUnitGroup units; inside a group the
+// query tile is the slow index and the unit the fast one.  Tiles at or beyond
+// the active length exit at once, and in a decode loop that is most tiles of
+// every unit: with the tile as the fast index the surviving workgroups would sit
+// at a fixed stride of the dispatch order, which the hardware maps onto a fixed
+// subset of the compute units (measured: the time did not drop at all when the
+// active length fell from 1024 to 256).  Runs of kUnitGroup live workgroups
+// spread over all of them, and the tiles of one unit still run close enough
+// together to share its K/V stream in L2.
+constexpr int kUnitGroup = 8;
 struct Place {
   int b, g, h, q0;
   bool valid;
@@ -176,14 +189,28 @@ __device__ __forceinline__ Place place(const AttnArgs &a, int qtile) {
   const int per_unit = rep * QT;
   const int n = blockIdx.x;
   const int m8 = n >> 3;
-  const int unit = (m8 / per_unit) * 8 + (n & 7);
-  const int wu = m8 % per_unit;
+  const int G = a.unit_group;
+  const int grp = m8 / (G * per_unit), r = m8 % (G * per_unit);
+  const int wu = r / G;
+  const int unit = (grp * G + r % G) * 8 + (n & 7);
   p.valid = unit < a.B * a.Hkv;
   p.b = unit / a.Hkv;
   p.g = unit % a.Hkv;
   p.h = p.g * rep + wu / QT;
   p.q0 = (wu % QT) * qtile;
   return p;
+}
+// group size (stored in a.unit_group) and number of workgroups of that placement
+inline int64_t place_grid(AttnArgs &a, int qtile) {
+  const int64_t QT = (a.S + qtile - 1) / qtile;
+  const int64_t units8 = (int64_t(a.B) * a.Hkv + 7) / 8;  // units per XCD
+  int64_t G = units8 < kUnitGroup ? units8 : kUnitGroup;
+#ifdef LSP_TUNE
+  if (getenv("LSP_ATTN_G")) G = atoi(getenv("LSP_ATTN_G"));
+#endif
+  a.unit_group = int32_t(G);
+  const int64_t groups = (units8 + G - 1) / G;
+  return groups * G * (a.Hq / a.Hkv) * QT * 8;
 }
 
 // Final step shared by both kernels: the WK partial results of every query
@@ -354,10 +381,8 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
 }
 
 template <int D, int WM, int WK>
-int32_t launch(const AttnArgs &a, hipStream_t st) {
-  const int64_t QT = (a.S + 32 * WM - 1) / (32 * WM);
-  const int64_t units = int64_t(a.B) * a.Hkv;
-  const int64_t nwg = (units + 7) / 8 * 8 * (a.Hq / a.Hkv) * QT;
+int32_t launch(AttnArgs a, hipStream_t st) {
+  const int64_t nwg = place_grid(a, 32 * WM);
   if (nwg > 0x7fffffff) {
     set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
     return LSP_ERR_UNSUPPORTED;
@@ -505,10 +530,8 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
 }
 
 template <int D, int WM, int OCC, int PD>
-int32_t launch_tile(const AttnArgs &a, hipStream_t st) {
-  const int64_t QT = (a.S + 32 * WM - 1) / (32 * WM);
-  const int64_t units = int64_t(a.B) * a.Hkv;
-  const int64_t nwg = (units + 7) / 8 * 8 * (a.Hq / a.Hkv) * QT;
+int32_t launch_tile(AttnArgs a, hipStream_t st) {
+  const int64_t nwg = place_grid(a, 32 * WM);
   if (nwg > 0x7fffffff) {
     set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
     return LSP_ERR_UNSUPPORTED;

@@ -15,11 +15,16 @@ from . import LayerTable, attn_step, commit, confidence, flip_update
 
 def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
                 prefix_len, suffix_len, tokens, kv_layers=None, gen_len=None, run_attention=False,
-                poll=1, max_steps=100000):
+                poll=1, max_steps=100000, stop_after=None, observer=None, timed=False):
     """logits_fn(step, prefix_len) -> device logits [B,S,V].  prefix_len,
     suffix_len, tokens and the caches in kv_layers (list of dicts q?, k_suf,
-    v_suf, k_cache, v_cache) are updated in place.  Returns dict(steps, flips,
-    flip_denominator, committed)."""
+    v_suf, k_cache, v_cache) are updated in place.
+    stop_after: leave the loop after that many steps even if positions remain.
+    observer(step, logits, conf, commit_out): called after every step's commit
+    (the tensors are reused by the next step: copy what is to be kept).
+    timed: bracket every step's library calls with HIP events on the current
+    stream and return their sum as lsp_ms (the logits callback is outside).
+    Returns dict(steps, flips, flip_denominator, committed[, lsp_ms, lsp_ms_steps])."""
     dev = prefix_len.device
     B = prefix_len.shape[0]
     G = int(gen_len if gen_len is not None else suffix_len.max().item())
@@ -33,20 +38,35 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     steps = 0
     out = conf = None
     attn_out = None
+    events = []
     while True:
         if steps % poll == 0 and int(suffix_len.max().item()) == 0:
             break
+        if stop_after is not None and steps >= stop_after:
+            break
         assert steps < max_steps
+        z = logits_fn(steps, prefix_len)
+        if timed:
+            events.append((torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)))
+            events[-1][0].record()
         if run_attention and kv_layers is not None:
             for L in kv_layers:
                 attn_out = attn_step(L["q"], L["k_suf"], L["v_suf"], L["k_cache"], L["v_cache"],
                                      prefix_len, suffix_len, out=attn_out)
-        z = logits_fn(steps, prefix_len)
         conf = confidence(z, suffix_len, out=conf)
         flip_update(conf[0], prefix_len, suffix_len, base, last_id, counters)
         out = commit(conf[2], conf[0], bitmap, V, tau, window, min_commit, snap_enabled,
                      prefix_len, suffix_len, tokens=tokens, layers=table, C=tokens.shape[1], out=out)
+        if timed:
+            events[-1][1].record()
+        if observer is not None:
+            observer(steps, z, conf, out)
         steps += 1
     c = counters.tolist()
     committed = int((prefix_len - base).sum().item())
-    return dict(steps=steps, flips=c[0], flip_denominator=c[1], committed=committed)
+    res = dict(steps=steps, flips=c[0], flip_denominator=c[1], committed=committed)
+    if timed:
+        torch.cuda.synchronize()
+        res["lsp_ms_steps"] = [a.elapsed_time(b) for a, b in events]
+        res["lsp_ms"] = sum(res["lsp_ms_steps"])
+    return res

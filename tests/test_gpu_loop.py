@@ -41,3 +41,72 @@ def test_small_loop_matches_oracle(lsp, oracle, tau, Lmin):
     for Lg, Lr in zip(lay_g, lay):
         assert torch.equal(Lg["k_cache"].cpu().view(torch.int16), Lr["k_cache"].view(torch.int16))
         assert torch.equal(Lg["v_cache"].cpu().view(torch.int16), Lr["v_cache"].view(torch.int16))
+
+
+def test_c5_full_size_first_steps_sampled(lsp, oracle):
+    """Config 5 at its full shape (batch 16, 32 layers, 1024 active rows, vocab
+    126464), first steps of the loop in the launch configuration bench.py uses.
+    Per step: the boundary outputs of every sequence against the oracle's commit
+    run on the step's (margin, id); sampled logits rows against the oracle's
+    confidence; sampled attention rows of one layer; the appended cache rows of
+    sampled layers equal the suffix rows they were copied from and the row after
+    them is untouched."""
+    from paper_2603_05454_amd.loop import decode_loop as gpu_loop
+    w = W.scaled(W.C5, layers=3)          # 3 of the 32 layers keep the test at a few GB
+    dev = "cuda"
+    _, bm = W.make_delimiters(w)
+    layers = [W.make_layer_kv(w, l, device=dev) for l in range(w.layers)]
+    pl, sl = (t.to(dev) for t in W.make_lengths(w))
+    tokens = W.make_tokens(w, w.C).to(dev)
+    fn = lambda step, p: W.make_process_logits(w, dev, step, p)[0]
+    g = torch.Generator().manual_seed(11)
+    seen = {"steps": 0, "total": torch.zeros(w.B, dtype=torch.int64)}
+
+    def observer(step, z, conf, out):
+        ids, prob, mar = (t.cpu() for t in conf)
+        L = out["commit_len"].cpu()
+        p_after, n_after = pl.cpu(), sl.cpu()
+        p0, n0 = p_after - L, n_after + L
+        # commit: oracle on the same (margin, id), state before the step
+        pr, nr = p0.clone(), n0.clone()
+        ref = oracle.commit(mar, ids, bm, w.V, w.tau, w.window, w.min_commit, 1, pr, nr, C=w.C)
+        for k in ref:
+            assert torch.equal(out[k].cpu(), ref[k]), (step, k)
+        assert torch.equal(pr, p_after) and torch.equal(nr, n_after)
+        # confidence: sampled active rows
+        for _ in range(6):
+            b = int(torch.randint(0, w.B, (1,), generator=g))
+            if int(n0[b]) == 0:
+                continue
+            i = int(torch.randint(0, int(n0[b]), (1,), generator=g))
+            ri, rp, rm = oracle.confidence(z[b, i].cpu().view(1, 1, -1))
+            assert int(ri) == int(ids[b, i]) and float(rm) == float(mar[b, i]), (step, b, i)
+            assert abs(float(rp) - float(prob[b, i])) <= 2e-2
+        # append: committed rows of every layer equal the suffix rows; the next row is still poison
+        for Lr in layers:
+            for b in range(w.B):
+                l = int(L[b])
+                if l:
+                    assert torch.equal(Lr["k_cache"][b, int(p0[b]): int(p_after[b])], Lr["k_suf"][b, :l])
+                    assert torch.equal(Lr["v_cache"][b, int(p0[b]): int(p_after[b])], Lr["v_suf"][b, :l])
+                if int(p_after[b]) < w.C:
+                    assert torch.all(Lr["k_cache"][b, int(p_after[b])].float() == W.POISON_F32)
+        seen["steps"] += 1
+        seen["total"] += L.long()
+
+    r = gpu_loop(fn, bm.to(dev), w.V, w.tau, w.window, w.min_commit, 1, pl, sl, tokens, kv_layers=layers,
+                 gen_len=w.gen_len, run_attention=True, stop_after=6, observer=observer)
+    assert r["steps"] == seen["steps"] == 6 and r["committed"] == int(seen["total"].sum())
+    # attention at the state the loop stopped in: sampled rows of layer 1 against the oracle
+    Lr = layers[1]
+    out = lsp.attn_step(Lr["q"], Lr["k_suf"], Lr["v_suf"], Lr["k_cache"], Lr["v_cache"], pl, sl)
+    torch.cuda.synchronize()
+    plc, slc = pl.cpu(), sl.cpu()
+    rows = []
+    for _ in range(24):
+        b = int(torch.randint(0, w.B, (1,), generator=g))
+        rows.append([b, int(torch.randint(0, int(slc[b]), (1,), generator=g)), int(torch.randint(0, w.Hq, (1,), generator=g))])
+    rows = torch.tensor(rows, dtype=torch.int32)
+    ref = oracle.attention(**{k: v.cpu() for k, v in Lr.items()}, prefix_len=plc, suffix_len=slc, rows=rows)
+    got = out[rows[:, 0].long().cuda(), rows[:, 1].long().cuda(), rows[:, 2].long().cuda()].float().cpu()
+    assert (got - ref).abs().max().item() <= 2e-2
