@@ -86,11 +86,13 @@ def confidence(logits, suffix_len=None):
 
 def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
            prefix_len, suffix_len, tokens=None, k_suf=None, v_suf=None, k_cache=None, v_cache=None,
-           C=None):
+           C=None, adaptive=False, alpha=0.25, beta=0.5, max_commit=0):
     """Boundary search + snap + commit + append.  Mutates tokens, prefix_len,
     suffix_len and the cache tensors IN PLACE (pass clones).  k_suf.. are lists
     of per-layer tensors ([B,S,Hkv,D] / [B,C,Hkv,D]) or None for scan only.
-    Returns dict(stable_mask, raw_boundary, snapped_boundary, commit_len, status_flags)."""
+    adaptive: choose the threshold per sequence so that L' falls in
+    [ceil(alpha N), floor(beta N)] (Eq. 2); max_commit > 0 caps the commit length.
+    Returns dict(stable_mask, raw_boundary, snapped_boundary, commit_len, status_flags, tau_used)."""
     B, S = margin.shape
     assert margin.dtype == torch.float32 and top1_id.dtype == torch.int32
     assert prefix_len.dtype == torch.int32 and suffix_len.dtype == torch.int32
@@ -117,13 +119,15 @@ def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
         "snapped_boundary": torch.zeros(B, dtype=torch.int32),
         "commit_len": torch.zeros(B, dtype=torch.int32),
         "status_flags": torch.zeros(B, dtype=torch.int32),
+        "tau_used": torch.zeros(B, dtype=torch.float32),
     }
     rc = lib().oracle_commit(kvdt, B, S, V, Hkv, D, C, layers, T,
                              ctypes.c_float(tau), int(window), int(min_commit), int(snap_enabled),
+                             int(bool(adaptive)), ctypes.c_float(alpha), ctypes.c_float(beta), int(max_commit),
                              _p(margin), _p(top1_id), _p(bitmap),
                              arrs[0], arrs[1], arrs[2], arrs[3],
                              _p(tokens), _p(prefix_len), _p(suffix_len),
                              _p(out["stable_mask"]), _p(out["raw_boundary"]), _p(out["snapped_boundary"]),
-                             _p(out["commit_len"]), _p(out["status_flags"]))
+                             _p(out["commit_len"]), _p(out["status_flags"]), _p(out["tau_used"]))
     assert rc == 0, rc
     return out

@@ -15,11 +15,13 @@ from . import commit, confidence
 
 
 def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
-                prefix_len, suffix_len, tokens, kv_layers=None, max_steps=100000, trace=False):
+                prefix_len, suffix_len, tokens, kv_layers=None, max_steps=100000, trace=False,
+                commit_kw=None):
     """logits_fn(step, prefix_len) -> [B,S,V] CPU tensor (row u = u-th active position).
     prefix_len / suffix_len / tokens / kv_layers (list of dicts with k_suf,
     v_suf [B,S,Hkv,D], row u = u-th active position, reused unchanged by every
     step, and k_cache, v_cache) are updated in place.
+    commit_kw: extra keyword arguments of oracle.commit (adaptive, alpha, beta, max_commit).
     Returns dict(steps, flips, flip_denominator, committed, per_step=[...])."""
     B = prefix_len.shape[0]
     P0 = prefix_len.clone()
@@ -40,9 +42,9 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
             flips += int(((cur != old) & seen).sum())
             denom += int(seen.sum())
             prev[b, done[b]:done[b] + n] = cur
-        kw = {}
+        kw = dict(commit_kw or {})
         if kv_layers is not None:
-            kw = dict(k_suf=[L["k_suf"] for L in kv_layers], v_suf=[L["v_suf"] for L in kv_layers],
+            kw.update(k_suf=[L["k_suf"] for L in kv_layers], v_suf=[L["v_suf"] for L in kv_layers],
                       k_cache=[L["k_cache"] for L in kv_layers], v_cache=[L["v_cache"] for L in kv_layers])
         out = commit(mar, ids, bitmap, V, tau, window, min_commit, snap_enabled,
                      prefix_len, suffix_len, tokens=tokens, C=tokens.shape[1], **kw)

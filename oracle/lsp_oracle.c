@@ -173,13 +173,67 @@ static int is_delim(const uint32_t *bitmap, int32_t id)
 }
 
 /*
+ * Adaptive threshold of Section 3.2 ("targeted block sizing", Eq. 2; Algorithm 1
+ * line 6): find a threshold tau_k whose run length L'(tau_k) lies in
+ * [lo, hi] = [ceil(alpha N), max(lo, floor(beta N))], via the prefix minimum
+ * pm[i] = min(margin[0..i]).
+ *
+ * L'(t) is the first i with margin[i] <= t (N if none), so a length a with
+ * 1 <= a < N is reachable by some threshold exactly when margin[a] <
+ * pm[a-1] (any t in [margin[a], pm[a-1]) gives it); a = N is reachable by any
+ * t < pm[N-1].  L0 is the length the caller's own threshold tau gives.
+ *   lo <= L0 <= hi : keep it (tau_k = tau).
+ *   L0 <  lo       : the SMALLEST reachable length in [lo, hi] (tau is lowered
+ *                    as little as possible); tau_k = margin[a], or -inf for a = N.
+ *   L0 >  hi       : the LARGEST reachable length in [lo, hi] (tau is raised as
+ *                    little as possible).
+ *   no reachable length in [lo, hi]: no threshold satisfies Eq. 2; the nearer
+ *                    interval bound is used (lo or hi), tau_k = NaN and
+ *                    *no_threshold = 1.
+ * lo and hi are computed with one single-precision multiplication each.
+ */
+static int adaptive_length(const float *mg, int N, int L0, float tau, float alpha, float beta,
+                           float *tau_k, int *no_threshold)
+{
+    int lo = (int)ceilf(alpha * (float)N);
+    int hi = (int)floorf(beta * (float)N);
+    if (lo < 0) lo = 0;
+    if (lo > N) lo = N;
+    if (hi > N) hi = N;
+    if (hi < lo) hi = lo;
+    *tau_k = tau;
+    if (L0 >= lo && L0 <= hi) return L0;
+    int first = -1, last = -1;          /* reachable lengths inside [lo, hi] */
+    float pm = INFINITY;                /* prefix minimum of margin[0..a-1] */
+    for (int a = 0; a <= N; ++a) {
+        int reachable = a == N ? 1 : (a == 0 ? 1 : mg[a] < pm);
+        if (reachable && a >= lo && a <= hi) {
+            if (first < 0) first = a;
+            last = a;
+        }
+        if (a < N && mg[a] < pm) pm = mg[a];
+    }
+    if (first < 0) {
+        *no_threshold = 1;
+        *tau_k = NAN;
+        return L0 < lo ? lo : hi;
+    }
+    int a = L0 < lo ? first : last;
+    *tau_k = a == N ? -INFINITY : mg[a];
+    return a;
+}
+
+/*
  * Boundary search, snap, commit and append for every sequence.
  *
  * mask_i = margin_i > tau (strict) for i < N;  L' = first i with mask_i = 0,
  * else N.  L_snap = the largest length j in [1, L'] with L' - j <= W whose
  * last token id[j-1] is a delimiter; L' itself if there is none, if snapping
  * is off or if L' = 0.  (window < 0 means no window limit.)
- * L = min(N, max(L_snap, L_min)), then clamped to the cache room C - P
+ * When `adaptive` is set, L' is replaced by adaptive_length() above (the mask
+ * output stays relative to the caller's tau); tau_used[b] receives tau_k.
+ * L = min(N, max(L_snap, L_min)), cut to max_commit when that is > 0 (the
+ * fixed-prefix variant of the sizing ablation, Table 2), then clamped to the cache room C - P
  * (status bit 0 set when that clamp bites) and to the token buffer room T - P
  * (status bit 1).
  * Commit: tokens[b, P..P+L) = id[b, 0..L); for every layer the first L suffix
@@ -188,12 +242,13 @@ static int is_delim(const uint32_t *bitmap, int32_t id)
  */
 int oracle_commit(int kv_dtype, int B, int S, int V, int Hkv, int D, int C, int layers, int T,
                   float tau, int window, int min_commit, int snap_enabled,
+                  int adaptive, float alpha, float beta, int max_commit,
                   const float *margin, const int32_t *top1_id, const uint32_t *bitmap,
                   const void *const *k_suf, const void *const *v_suf,
                   void *const *k_cache, void *const *v_cache,
                   int32_t *tokens, int32_t *prefix_len, int32_t *suffix_len,
                   uint8_t *stable_mask, int32_t *raw_boundary, int32_t *snapped_boundary,
-                  int32_t *commit_len, int32_t *status_flags)
+                  int32_t *commit_len, int32_t *status_flags, float *tau_used)
 {
     (void)V;
     size_t esz = kv_dtype == 0 ? 4 : 2;
@@ -208,6 +263,11 @@ int oracle_commit(int kv_dtype, int B, int S, int V, int Hkv, int D, int C, int 
         int Lp = N;
         for (int i = 0; i < N; ++i)
             if (!mk[i]) { Lp = i; break; }
+        float tk = tau;
+        int no_threshold = 0;
+        if (adaptive && N > 0)
+            Lp = adaptive_length(mg, N, Lp, tau, alpha, beta, &tk, &no_threshold);
+        if (tau_used) tau_used[b] = tk;
         int Ls = Lp;
         if (snap_enabled && Lp > 0) {
             for (int j = Lp; j >= 1; --j) {
@@ -217,8 +277,9 @@ int oracle_commit(int kv_dtype, int B, int S, int V, int Hkv, int D, int C, int 
         }
         int L = Ls > min_commit ? Ls : min_commit;
         if (L > N) L = N;
-        int flag = 0;
-        if (L > C - P) { L = C - P > 0 ? C - P : 0; flag = 1; }
+        if (max_commit > 0 && L > max_commit) L = max_commit;
+        int flag = no_threshold ? 4 : 0;
+        if (L > C - P) { L = C - P > 0 ? C - P : 0; flag |= 1; }
         if (tokens && L > T - P) { L = T - P > 0 ? T - P : 0; flag |= 2; }
         raw_boundary[b] = Lp;
         snapped_boundary[b] = Ls;
