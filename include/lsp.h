@@ -58,6 +58,7 @@ typedef enum {
 /* Bits of status_flags[b] written by lsp_commit. */
 #define LSP_FLAG_CACHE_FULL 1  /* commit length was cut to the cache room C - P_b */
 #define LSP_FLAG_TOKENS_FULL 2 /* commit length was cut to the token buffer room T - P_b */
+#define LSP_FLAG_NO_THRESHOLD 4 /* adaptive sizing: no threshold puts L' in [alpha N, beta N]; the nearer bound was used */
 
 const char *lsp_version(void);
 const char *lsp_last_error(void);
@@ -131,14 +132,28 @@ int32_t lsp_confidence(int32_t dtype, const void *logits, int32_t B, int32_t S, 
  *
  * Per sequence b, with N = N_b and P = P_b on entry:
  *   stable_mask[b,i] = (i < N and margin[b,i] > tau)           (strict)
- *   raw_boundary[b]  = L' = first i with stable_mask = 0, else N
+ *   raw_boundary[b]  = L' = first i with stable_mask = 0, else N; with
+ *                      adaptive = 1 the threshold is chosen per sequence instead
+ *                      (Section 3.2 "targeted block sizing", Eq. 2; Algorithm 1
+ *                      line 6): with lo = ceil(alpha N), hi = max(lo, floor(beta N))
+ *                      (one fp32 multiplication each) and L0 the length tau
+ *                      gives, L' = L0 if lo <= L0 <= hi; otherwise the smallest
+ *                      (L0 < lo) or largest (L0 > hi) length in [lo, hi] that
+ *                      SOME threshold produces - a length a < N is produced by
+ *                      a threshold exactly when margin[a] is below the minimum
+ *                      of margin[0..a-1], a = N always - and if there is none,
+ *                      lo resp. hi with LSP_FLAG_NO_THRESHOLD set.  tau_used[b]
+ *                      = tau, margin[a] (-inf for a = N) or NaN in these cases.
+ *                      stable_mask stays relative to tau.
  *   snapped_boundary = the largest length j in [1, L'] with L' - j <= window
  *                      whose last token top1_id[b,j-1] is in the delimiter
  *                      set; L' when there is none, when snap_enabled = 0 or
  *                      when L' = 0.  window < 0 = no limit.
  *   commit_len[b]    = L = min(N, max(snapped_boundary, min_commit)), cut to
- *                      the cache room C - P and the token room T - P (a cut
- *                      sets the matching LSP_FLAG_* bit in status_flags[b]).
+ *                      max_commit when that is > 0 (the fixed-prefix variant of
+ *                      the sizing ablation, Table 2), then to the cache room
+ *                      C - P and the token room T - P (a cut to room sets the
+ *                      matching LSP_FLAG_* bit in status_flags[b]).
  *   tokens[b, P..P+L) = top1_id[b, 0..L)
  *   for every layer: cache rows [P, P+L) = suffix rows [0, L), K and V - one
  *                      contiguous block of L*Hkv*D elements each
@@ -156,6 +171,9 @@ typedef struct {
   int32_t snap_enabled;
   int64_t suf_batch_stride;   /* elements between sequences in a suffix K/V buffer; 0 = S*Hkv*D */
   int64_t cache_batch_stride; /* elements between sequences in a cache; 0 = C*Hkv*D */
+  int32_t adaptive;       /* 1 = choose the threshold per sequence (Eq. 2) */
+  float alpha, beta;      /* acceptance interval, 0 < alpha <= beta <= 1 (read when adaptive) */
+  int32_t max_commit;     /* > 0: upper bound of the commit length; 0 = none */
 } lsp_commit_desc;
 
 size_t lsp_commit_workspace_bytes(const lsp_commit_desc *desc);
@@ -171,7 +189,7 @@ size_t lsp_commit_workspace_bytes(const lsp_commit_desc *desc);
  * tokens: device int32 [B,T] in/out, or NULL.  prefix_len, suffix_len: device
  * int32[B] in/out.  stable_mask: device uint8 [B,S].  raw_boundary,
  * snapped_boundary, commit_len, status_flags: device int32[B] out
- * (status_flags may be NULL).
+ * (status_flags may be NULL).  tau_used: device fp32[B] out, or NULL.
  */
 int32_t lsp_commit(const lsp_commit_desc *desc, const float *margin, const int32_t *top1_id,
                    const uint32_t *delimiter_bitmap,
@@ -179,7 +197,7 @@ int32_t lsp_commit(const lsp_commit_desc *desc, const float *margin, const int32
                    void *const *k_cache_layers, void *const *v_cache_layers,
                    int32_t *tokens, int32_t *prefix_len, int32_t *suffix_len,
                    uint8_t *stable_mask, int32_t *raw_boundary, int32_t *snapped_boundary,
-                   int32_t *commit_len, int32_t *status_flags,
+                   int32_t *commit_len, int32_t *status_flags, float *tau_used,
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------- *

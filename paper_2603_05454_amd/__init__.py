@@ -39,7 +39,8 @@ class CommitDesc(ctypes.Structure):
                 ("C", ctypes.c_int32), ("num_layers", ctypes.c_int32), ("T", ctypes.c_int32),
                 ("tau", ctypes.c_float), ("window", ctypes.c_int32), ("min_commit", ctypes.c_int32),
                 ("snap_enabled", ctypes.c_int32), ("suf_batch_stride", ctypes.c_int64),
-                ("cache_batch_stride", ctypes.c_int64)]
+                ("cache_batch_stride", ctypes.c_int64), ("adaptive", ctypes.c_int32),
+                ("alpha", ctypes.c_float), ("beta", ctypes.c_float), ("max_commit", ctypes.c_int32)]
 
 
 EXPORTS = ["lsp_version", "lsp_last_error", "lsp_attn_workspace_bytes", "lsp_attn_step",
@@ -181,10 +182,11 @@ class LayerTable:
 
 
 def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
-           prefix_len, suffix_len, tokens=None, layers: LayerTable | None = None, C=None, out=None):
+           prefix_len, suffix_len, tokens=None, layers: LayerTable | None = None, C=None, out=None,
+           adaptive=False, alpha=0.25, beta=0.5, max_commit=0):
     """lsp_commit.  Mutates tokens, prefix_len, suffix_len and the caches of
     `layers` in place.  Returns dict(stable_mask, raw_boundary, snapped_boundary,
-    commit_len, status_flags)."""
+    commit_len, status_flags, tau_used)."""
     _dev(margin, top1_id, bitmap, prefix_len, suffix_len, tokens)
     B, S = margin.shape
     dev = margin.device
@@ -192,8 +194,10 @@ def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
         out = {"stable_mask": torch.empty((B, S), dtype=torch.uint8, device=dev)}
         for k in ("raw_boundary", "snapped_boundary", "commit_len", "status_flags"):
             out[k] = torch.empty(B, dtype=torch.int32, device=dev)
+        out["tau_used"] = torch.empty(B, dtype=torch.float32, device=dev)
     d = CommitDesc(B=B, S=S, V=V, tau=float(tau), window=int(window), min_commit=int(min_commit),
-                   snap_enabled=int(snap_enabled), T=0 if tokens is None else tokens.shape[1])
+                   snap_enabled=int(snap_enabled), T=0 if tokens is None else tokens.shape[1],
+                   adaptive=int(bool(adaptive)), alpha=float(alpha), beta=float(beta), max_commit=int(max_commit))
     if layers is not None:
         assert layers.S == S
         d.kv_dtype, d.Hkv, d.D, d.C, d.num_layers = layers.kv_dtype, layers.Hkv, layers.D, layers.C, layers.n
@@ -207,7 +211,8 @@ def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
                           arrs[0], arrs[1], arrs[2], arrs[3], _ptr(tokens), _ptr(prefix_len),
                           _ptr(suffix_len), _ptr(out["stable_mask"]), _ptr(out["raw_boundary"]),
                           _ptr(out["snapped_boundary"]), _ptr(out["commit_len"]),
-                          _ptr(out["status_flags"]), ctypes.c_void_p(0), ctypes.c_size_t(0), _stream())
+                          _ptr(out["status_flags"]), _ptr(out.get("tau_used")), ctypes.c_void_p(0),
+                          ctypes.c_size_t(0), _stream())
     _check(rc, "lsp_commit")
     return out
 

@@ -11,6 +11,8 @@
 // L * Hkv * D elements from the suffix buffer to cache row P with 16-byte
 // loads and stores; the block length is read from device memory, so the host
 // never learns L and the grid is sized for the worst case with early exit.
+#include <limits.h>
+
 #include "lsp_common.h"
 
 namespace lsp {
@@ -23,14 +25,16 @@ constexpr int kScanThreads = 256;
 __global__ __launch_bounds__(kScanThreads) void boundary_kernel(
     const float *__restrict__ margin, const int32_t *__restrict__ top1_id,
     const uint32_t *__restrict__ bitmap, int S, int V, int C, int T, float tau, int window,
-    int min_commit, int snap_enabled, int32_t *__restrict__ tokens,
+    int min_commit, int snap_enabled, int adaptive, float alpha, float beta, int max_commit,
+    int32_t *__restrict__ tokens,
     int32_t *__restrict__ prefix_len, int32_t *__restrict__ suffix_len,
     uint8_t *__restrict__ stable_mask, int32_t *__restrict__ raw_boundary,
     int32_t *__restrict__ snapped_boundary, int32_t *__restrict__ commit_len,
-    int32_t *__restrict__ status_flags) {
+    int32_t *__restrict__ status_flags, float *__restrict__ tau_used) {
   const int b = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  __shared__ int s_first, s_snap;
+  __shared__ int s_first, s_snap, s_lo_hit, s_hi_hit;
+  __shared__ float s_min[kScanThreads];
   const int N = min(max(suffix_len[b], 0), S);
   const int P = max(prefix_len[b], 0);
   const float *mg = margin + int64_t(b) * S;
@@ -39,6 +43,8 @@ __global__ __launch_bounds__(kScanThreads) void boundary_kernel(
   if (tid == 0) {
     s_first = N;
     s_snap = 0;
+    s_lo_hit = INT_MAX;
+    s_hi_hit = -1;
   }
   __syncthreads();
 
@@ -54,7 +60,61 @@ __global__ __launch_bounds__(kScanThreads) void boundary_kernel(
   }
   if (lane == 0 && first < N) atomicMin(&s_first, first);
   __syncthreads();
-  const int Lp = s_first;
+  int Lp = s_first;
+  float tk = tau;
+  int flag = 0;
+
+  // Adaptive threshold (Eq. 2): a length a in [1, N) is produced by some threshold
+  // exactly when margin[a] is a strict new minimum of margin[0..a].  Every thread
+  // owns a contiguous chunk of positions: chunk minima, an exclusive prefix
+  // minimum across threads in LDS, then a walk over the chunk that keeps the
+  // first and the last such length inside [lo, hi].
+  if (adaptive && N > 0) {
+    int lo = int(ceilf(__fmul_rn(alpha, float(N))));
+    int hi = int(floorf(__fmul_rn(beta, float(N))));
+    lo = min(max(lo, 0), N);
+    hi = max(min(hi, N), lo);
+    if (Lp < lo || Lp > hi) {  // uniform over the workgroup
+      const int chunk = (N + kScanThreads - 1) / kScanThreads;
+      const int i0 = min(tid * chunk, N), i1 = min(i0 + chunk, N);
+      float m = INFINITY;
+      for (int i = i0; i < i1; ++i) m = fminf(m, mg[i]);
+      s_min[tid] = m;
+      __syncthreads();
+      for (int d = 1; d < kScanThreads; d <<= 1) {  // inclusive prefix minimum over threads
+        const float other = tid >= d ? s_min[tid - d] : INFINITY;
+        __syncthreads();
+        s_min[tid] = fminf(s_min[tid], other);
+        __syncthreads();
+      }
+      float pm = tid > 0 ? s_min[tid - 1] : INFINITY;  // minimum of everything before this chunk
+      int first = INT_MAX, last = -1;
+      for (int i = i0; i < i1; ++i) {
+        const float x = mg[i];
+        if (x < pm) {
+          if (i >= lo && i <= hi && i >= 1) {
+            first = min(first, i);
+            last = i;
+          }
+          pm = x;
+        }
+      }
+      if (lo == 0 && tid == 0) first = 0;  // length 0 is produced by any threshold >= margin[0]
+      if (first != INT_MAX) atomicMin(&s_lo_hit, first);
+      if (last >= 0) atomicMax(&s_hi_hit, last);
+      if (tid == 0 && hi == N) atomicMax(&s_hi_hit, N), atomicMin(&s_lo_hit, N);  // N: any threshold below every margin
+      __syncthreads();
+      const int fst = s_lo_hit, lst = s_hi_hit;
+      if (lst < 0) {  // no threshold satisfies Eq. 2
+        flag |= LSP_FLAG_NO_THRESHOLD;
+        tk = __int_as_float(0x7fc00000);
+        Lp = Lp < lo ? lo : hi;
+      } else {
+        Lp = Lp < lo ? fst : lst;
+        tk = Lp == N ? -INFINITY : mg[Lp];
+      }
+    }
+  }
 
   // last delimiter inside the window: candidate lengths j = Lp, Lp-1, ...
   if (snap_enabled && Lp > 0) {
@@ -73,7 +133,7 @@ __global__ __launch_bounds__(kScanThreads) void boundary_kernel(
   __syncthreads();
   const int Ls = s_snap > 0 ? s_snap : Lp;
   int L = min(N, max(Ls, min_commit));
-  int flag = 0;
+  if (max_commit > 0) L = min(L, max_commit);
   if (L > C - P) {
     L = max(C - P, 0);
     flag |= LSP_FLAG_CACHE_FULL;
@@ -89,6 +149,7 @@ __global__ __launch_bounds__(kScanThreads) void boundary_kernel(
     snapped_boundary[b] = Ls;
     commit_len[b] = L;
     if (status_flags != nullptr) status_flags[b] = flag;
+    if (tau_used != nullptr) tau_used[b] = tk;
     prefix_len[b] = P + L;
     suffix_len[b] = N - L;
   }
@@ -142,7 +203,7 @@ extern "C" int32_t lsp_commit(const lsp_commit_desc *d, const float *margin, con
                               int32_t *tokens, int32_t *prefix_len, int32_t *suffix_len,
                               uint8_t *stable_mask, int32_t *raw_boundary,
                               int32_t *snapped_boundary, int32_t *commit_len,
-                              int32_t *status_flags, void *workspace, size_t workspace_bytes,
+                              int32_t *status_flags, float *tau_used, void *workspace, size_t workspace_bytes,
                               void *stream) {
   using namespace lsp;
   (void)workspace;
@@ -158,6 +219,9 @@ extern "C" int32_t lsp_commit(const lsp_commit_desc *d, const float *margin, con
   LSP_CHECK_ARG(!d->snap_enabled || delimiter_bitmap, "lsp_commit: snapping needs a delimiter bitmap");
   LSP_CHECK_ARG(tokens == nullptr || d->T > 0, "lsp_commit: token buffer needs T > 0");
   LSP_CHECK_ARG(d->num_layers >= 0, "lsp_commit: num_layers < 0");
+  LSP_CHECK_ARG(d->max_commit >= 0, "lsp_commit: max_commit must be >= 0");
+  LSP_CHECK_ARG(!d->adaptive || (d->alpha > 0.f && d->alpha <= d->beta && d->beta <= 1.f),
+                "lsp_commit: adaptive sizing needs 0 < alpha <= beta <= 1 (got %g, %g)", double(d->alpha), double(d->beta));
   int64_t row_bytes = 0, suf_bb = 0, cache_bb = 0;
   if (d->num_layers > 0) {
     LSP_CHECK_ARG(d->kv_dtype == LSP_F32 || d->kv_dtype == LSP_BF16, "lsp_commit: unknown kv_dtype");
@@ -183,8 +247,8 @@ extern "C" int32_t lsp_commit(const lsp_commit_desc *d, const float *margin, con
   hipStream_t st = static_cast<hipStream_t>(stream);
   boundary_kernel<<<d->B, kScanThreads, 0, st>>>(
       margin, top1_id, delimiter_bitmap, d->S, d->V, d->C, d->T, d->tau, d->window, d->min_commit,
-      d->snap_enabled, tokens, prefix_len, suffix_len, stable_mask, raw_boundary, snapped_boundary,
-      commit_len, status_flags);
+      d->snap_enabled, d->adaptive, d->alpha, d->beta, d->max_commit, tokens, prefix_len, suffix_len,
+      stable_mask, raw_boundary, snapped_boundary, commit_len, status_flags, tau_used);
   LSP_CHECK_LAUNCH("lsp_commit: boundary launch");
   if (d->num_layers > 0) {
     const int64_t max_bytes = int64_t(d->S) * row_bytes;

@@ -15,10 +15,11 @@ from . import LayerTable, attn_step, commit, confidence, flip_update
 
 def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
                 prefix_len, suffix_len, tokens, kv_layers=None, gen_len=None, run_attention=False,
-                poll=1, max_steps=100000, stop_after=None, observer=None, timed=False):
+                poll=1, max_steps=100000, stop_after=None, observer=None, timed=False, commit_kw=None):
     """logits_fn(step, prefix_len) -> device logits [B,S,V].  prefix_len,
     suffix_len, tokens and the caches in kv_layers (list of dicts q?, k_suf,
     v_suf, k_cache, v_cache) are updated in place.
+    commit_kw: extra keyword arguments of commit() (adaptive, alpha, beta, max_commit).
     stop_after: leave the loop after that many steps even if positions remain.
     observer(step, logits, conf, commit_out): called after every step's commit
     (the tensors are reused by the next step: copy what is to be kept).
@@ -56,7 +57,8 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
         conf = confidence(z, suffix_len, out=conf)
         flip_update(conf[0], prefix_len, suffix_len, base, last_id, counters)
         out = commit(conf[2], conf[0], bitmap, V, tau, window, min_commit, snap_enabled,
-                     prefix_len, suffix_len, tokens=tokens, layers=table, C=tokens.shape[1], out=out)
+                     prefix_len, suffix_len, tokens=tokens, layers=table, C=tokens.shape[1], out=out,
+                     **(commit_kw or {}))
         if timed:
             events[-1][1].record()
         if observer is not None:

@@ -26,8 +26,16 @@ def _bitmap(ids, V=V):
     return torch.where(words >= 2**31, words - 2**32, words).to(torch.int32)
 
 
-def _both(lsp, oracle, margin, ids, bm, Vv, tau, Wn, Lmin, snap, pl, sl, tokens=None, layers=None, C=None):
-    """Run oracle (CPU clones) and HIP (GPU clones); compare every output."""
+def _same(a, b):
+    """Bit-for-bit equal; NaN (the 'no threshold' marker of tau_used) equals NaN."""
+    if a.dtype.is_floating_point:
+        return torch.equal(torch.isnan(a), torch.isnan(b)) and torch.equal(a[~torch.isnan(a)], b[~torch.isnan(b)])
+    return torch.equal(a, b)
+
+
+def _both(lsp, oracle, margin, ids, bm, Vv, tau, Wn, Lmin, snap, pl, sl, tokens=None, layers=None, C=None, **sizing):
+    """Run oracle (CPU clones) and HIP (GPU clones); compare every output.
+    sizing: adaptive / alpha / beta / max_commit, passed to both sides."""
     pl_r, sl_r = pl.clone(), sl.clone()
     tok_r = None if tokens is None else tokens.clone()
     kw = {}
@@ -36,7 +44,7 @@ def _both(lsp, oracle, margin, ids, bm, Vv, tau, Wn, Lmin, snap, pl, sl, tokens=
         lay_r = [{k: v.clone() for k, v in L.items()} for L in layers]
         kw = dict(k_suf=[L["k_suf"] for L in lay_r], v_suf=[L["v_suf"] for L in lay_r],
                   k_cache=[L["k_cache"] for L in lay_r], v_cache=[L["v_cache"] for L in lay_r])
-    ref = oracle.commit(margin, ids, bm, Vv, tau, Wn, Lmin, snap, pl_r, sl_r, tokens=tok_r, C=C, **kw)
+    ref = oracle.commit(margin, ids, bm, Vv, tau, Wn, Lmin, snap, pl_r, sl_r, tokens=tok_r, C=C, **kw, **sizing)
     pl_g, sl_g = pl.cuda(), sl.cuda()
     tok_g = None if tokens is None else tokens.cuda()
     table = None
@@ -46,10 +54,10 @@ def _both(lsp, oracle, margin, ids, bm, Vv, tau, Wn, Lmin, snap, pl, sl, tokens=
         table = lsp.LayerTable([L["k_suf"] for L in lay_g], [L["v_suf"] for L in lay_g],
                                [L["k_cache"] for L in lay_g], [L["v_cache"] for L in lay_g])
     got = lsp.commit(margin.cuda(), ids.cuda(), bm.cuda(), Vv, tau, Wn, Lmin, snap, pl_g, sl_g,
-                     tokens=tok_g, layers=table, C=C)
+                     tokens=tok_g, layers=table, C=C, **sizing)
     torch.cuda.synchronize()
     for k in ref:
-        assert torch.equal(got[k].cpu(), ref[k]), k
+        assert _same(got[k].cpu(), ref[k]), k
     assert torch.equal(pl_g.cpu(), pl_r) and torch.equal(sl_g.cpu(), sl_r)
     if tokens is not None:
         assert torch.equal(tok_g.cpu(), tok_r)
@@ -178,3 +186,60 @@ def test_many_layers_more_than_one_launch(lsp, oracle):
     margin[0, 9] = 0
     ids = torch.full((2, 16), OTHER, dtype=torch.int32)
     _both(lsp, oracle, margin, ids, _bitmap([]), V, 0.9, 16, 1, 1, pl, sl, layers=layers)
+
+
+# ---- adaptive threshold (Section 3.2 targeted block sizing, Eq. 2) and commit cap (Table 2) ----
+@pytest.mark.parametrize("alpha,beta", [(0.25, 0.5), (0.5, 0.5), (0.2, 1.0), (0.75, 0.75)])
+def test_adaptive_every_small_margin_vector(lsp, oracle, alpha, beta):
+    N = 5
+    vals = [1.0, 2.0, 3.0, 4.0]
+    rows = list(itertools.product(vals, repeat=N))
+    margin = torch.tensor(rows, dtype=torch.float32)
+    B = len(rows)
+    ids = torch.tensor([[DELIM if (b >> i) & 1 else OTHER for i in range(N)] for b in range(B)], dtype=torch.int32)
+    for tau0 in (0.5, 2.0, 2.5, 4.0):
+        pl = torch.zeros(B, dtype=torch.int32)
+        sl = torch.tensor([N - (b % 7 == 0) * (b % 4) for b in range(B)], dtype=torch.int32)
+        _both(lsp, oracle, margin, ids, _bitmap([DELIM]), V, tau0, 2, 1, 1, pl, sl, C=16,
+              adaptive=True, alpha=alpha, beta=beta)
+
+
+@pytest.mark.parametrize("tau0", [-float("inf"), 0.3, 0.9, float("inf")])
+def test_adaptive_long_ragged_rows(lsp, oracle, tau0):
+    """Rows longer than one position per thread, lengths that end inside chunks,
+    quantised margins (ties), an empty suffix; three acceptance intervals."""
+    S = 1500
+    g = torch.Generator().manual_seed(4)
+    B = 12
+    margin = torch.rand((B, S), generator=g)
+    margin[0] = torch.linspace(3.0, 1.0, S)                          # strictly decreasing: every length reachable
+    margin[1] = 2.0                                                  # constant: only 0 and N reachable
+    margin[2] = (margin[2] * 8).floor() / 8                          # heavy ties
+    margin[3, :700] += 1.0
+    margin[4, 0] = 0.0                                               # unstable at once
+    ids = torch.randint(0, 4096, (B, S), generator=g, dtype=torch.int32)
+    bm = _bitmap(torch.randperm(4096, generator=g)[:300].tolist(), 4096)
+    sl0 = torch.tensor([1500, 1500, 1499, 1024, 1500, 1, 2, 257, 0, 777, 1300, 64], dtype=torch.int32)
+    for alpha, beta in [(0.25, 0.5), (0.1, 0.1), (0.6, 1.0)]:
+        pl = torch.zeros(B, dtype=torch.int32)
+        ref = _both(lsp, oracle, margin, ids, bm, 4096, tau0, 16, 1, 1, pl, sl0.clone(), C=4096,
+                    adaptive=True, alpha=alpha, beta=beta)
+        for b in range(B):
+            n = int(sl0[b])
+            if n:
+                lo = min(n, int(torch.ceil(torch.tensor(alpha, dtype=torch.float32) * n)))
+                hi = max(lo, min(n, int(torch.floor(torch.tensor(beta, dtype=torch.float32) * n))))
+                assert lo <= int(ref["raw_boundary"][b]) <= hi                 # Eq. 2 holds for every sequence
+
+
+def test_commit_cap_and_adaptive_with_append(lsp, oracle):
+    w = W.scaled(W.C1, B=3, S=48, P=8, C=64, Hq=2, Hkv=2, D=64, V=V, layers=2, dtype="bf16")
+    pl, sl = W.make_lengths(w)
+    layers = [W.make_layer_kv(w, l) for l in range(2)]
+    g = torch.Generator().manual_seed(2)
+    margin = 3.0 * torch.rand((3, 48), generator=g)
+    ids = torch.randint(0, V, (3, 48), generator=g, dtype=torch.int32)
+    tokens = torch.full((3, 64), -1, dtype=torch.int32)
+    for kw in (dict(max_commit=5), dict(adaptive=True, alpha=0.25, beta=0.5), dict(adaptive=True, alpha=0.25, beta=0.5, max_commit=7)):
+        _both(lsp, oracle, margin, ids, _bitmap([5, 6, 7]), V, 0.9, 16, 1, 1, pl.clone(), sl.clone(), tokens=tokens.clone(),
+              layers=[{k: v.clone() for k, v in L.items()} for L in layers], **kw)
