@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--sizing", default="tau", choices=["tau", "adaptive", "full"],
+                    help="c5: fixed threshold (default), adaptive threshold (Eq. 2, [0.25, 0.5]) or the Full baseline (1 position per step)")
     ap.add_argument("--loop-steps", type=int, default=0, help="c5: stop the decode loop after this many steps (0 = run to the end)")
     ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -283,7 +285,7 @@ def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True, overl
     return value, ms_per_step, config, roofline, cpu
 
 
-def run_loop_workload(max_steps=0):
+def run_loop_workload(max_steps=0, sizing="tau"):
     """Config 5: the whole decode loop (Algorithm 1 lines 3-11) at LLaDA-8B shape, batch 16,
     prompt 512, 1024 generated positions, all 32 layers' attention and KV append every step.
     The step's logits come from the seeded synthetic process (workloads.make_process_logits),
@@ -301,15 +303,23 @@ def run_loop_workload(max_steps=0):
     pl, sl = W.make_lengths(w, device=dev)
     tokens = W.make_tokens(w, w.C).to(dev)
     fn = lambda step, p: W.make_process_logits(w, dev, step, p)[0]
+    # sizing: "tau" = fixed margin threshold (the configuration BASELINE.json names); "adaptive" = the
+    # threshold chosen per step so that L' lies in [N/4, N/2] (Eq. 2 with Section 4.1's interval);
+    # "full" = the paper's Full baseline, one position per step (T_max = generation length)
+    tau, kw = w.tau, {}
+    if sizing == "adaptive":
+        kw = dict(adaptive=True, alpha=0.25, beta=0.5)
+    elif sizing == "full":
+        tau = float("inf")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    r = decode_loop(fn, bitmap.to(dev), w.V, w.tau, w.window, w.min_commit, 1, pl, sl, tokens,
+    r = decode_loop(fn, bitmap.to(dev), w.V, tau, w.window, w.min_commit, 1, pl, sl, tokens,
                     kv_layers=layers, gen_len=w.gen_len, run_attention=True, timed=True,
-                    stop_after=max_steps or None)
+                    stop_after=max_steps or None, commit_kw=kw)
     wall = time.perf_counter() - t0
     lsp_s = r["lsp_ms"] * 1e-3
     config = {"workload": w.name, "B": w.B, "layers": w.layers, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
-              "P": w.P, "gen_len": w.gen_len, "C": w.C, "V": w.V, "tau": w.tau, "window": w.window,
+              "P": w.P, "gen_len": w.gen_len, "C": w.C, "V": w.V, "tau": tau, "window": w.window, "sizing": sizing,
               "loop_steps": r["steps"], "committed_tokens": r["committed"], "flips": r["flips"],
               "flip_rate": round(r["flips"] / max(1, r["flip_denominator"]), 5),
               "ms_at_steps": {str(i): round(r["lsp_ms_steps"][i], 3)
@@ -348,7 +358,7 @@ def main():
         return
     K, Wm = args.steps, args.warmup
     if args.workload == "c5":
-        value, ms, config = run_loop_workload(args.loop_steps)
+        value, ms, config = run_loop_workload(args.loop_steps, args.sizing)
         print(json.dumps({"metric": "committed tokens/sec + per-step latency (ms), LLaDA-8B shape, 1 MI355X",
                           "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": config["loop_steps"],
                           "warmup": 0, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
