@@ -10,13 +10,12 @@
 //     layout of the second product  O^T[d, query] = V^T . P^T  (the contraction
 //     order over keys is the accumulator's row order, and V^T is read in that
 //     same order), so P never goes through LDS.
-// K blocks (32 keys) go from global memory straight into the A-operand
-// registers (a lane reads 16 bytes of its key's row per 16-wide d-step); V
-// blocks are staged row-major in a wave-private LDS region and read back with
-// the LDS transpose load (ds_read_tr16_b64), which hands each lane four keys
-// of its d column.  Waves never synchronise inside the key loop; block j+1's
-// global loads are in flight while block j goes through the soft-max and the
-// second product, and two waves per SIMD cover each other's waits.
+// K and V blocks (32 keys) are fetched with coalesced 16-byte loads and staged
+// row-major in LDS; K fragments are read back as 16-byte row pieces, V^T
+// fragments with the LDS transpose load (ds_read_tr16_b64), which hands each
+// lane four keys of its d column.  Block j+1's global loads are in flight while
+// block j goes through the products and the soft-max, and two waves per SIMD
+// cover each other's waits.
 //
 // The soft-max reference m only moves when a block maximum exceeds it by more
 // than 8 octaves, so the accumulator rescale is a cold, wave-uniform branch;
@@ -87,11 +86,13 @@ __device__ __forceinline__ float half_sum(float x) {
 
 template <int D>
 struct Geo {
+  static constexpr int KPITCH = D * 2 + 16;   // bytes per staged K row: 16 mod 256 keeps 16-byte column reads conflict-free
   static constexpr int VPITCH = D * 2 + 64;   // bytes per staged V row: 64 mod 256 keeps the transpose reads conflict-free
   static constexpr int OPITCH = D * 4 + 16;   // bytes per merged O row (fp32): 16 mod 256 for 16-byte column writes
+  static constexpr int KBYTES = 32 * KPITCH;
   static constexpr int VBYTES = 32 * VPITCH;
   static constexpr int OBYTES = 32 * OPITCH + 2 * 32 * 4;  // O^T block + m[32] + l[32]
-  static constexpr int WAVE_LDS = VBYTES > OBYTES ? VBYTES : OBYTES;
+  static constexpr int WAVE_LDS = KBYTES + VBYTES > OBYTES ? KBYTES + VBYTES : OBYTES;
 };
 
 // Second half of a 32-key block, shared by both kernels: soft-max of the score
@@ -287,6 +288,7 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
   constexpr int VL = D / 16;  // 16-byte V loads per lane per block (32 rows * D*2 bytes / 64 lanes / 16)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const Place pl = place(a, 32 * WM);
   if (!pl.valid) return;
   const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
@@ -294,7 +296,6 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
   if (q0 >= N) return;
   const int P = min(max(a.prefix_len[b], 0), a.C);
   const int T = P + N;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WK, wk = wave % WK;
   const int lq = lane & 31, hf = lane >> 5;
   unsigned char *wlds = smem + wave * G::WAVE_LDS;
@@ -321,62 +322,55 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
 
   const int NB = (T + 31) >> 5;  // 32-key blocks; this wave takes wk, wk+WK, ...
 
-  auto krow = [&](int t) -> const uint16_t * {
+  // K and V blocks take the same way: coalesced 16-byte loads (a wave-wide load
+  // covers whole rows: lane -> (row, 16-byte column)), a wave-private LDS stage,
+  // and fragment reads from there.  (Reading K fragments straight from global
+  // memory costs four times the address-unit cycles: every load touches 32 rows
+  // for 32 bytes each, and at small sizes those cycles are the critical path.)
+  auto row_ptr = [&](const uint16_t *cache, const uint16_t *suf, int t) -> const uint16_t * {
     t = min(t, T - 1);
-    return t < P ? kc + int64_t(t) * a.cs[1] : ks + int64_t(t - P) * a.ks[1];
+    return t < P ? cache + int64_t(t) * a.cs[1] : suf + int64_t(t - P) * a.ks[1];
   };
-  auto vrow = [&](int t) -> const uint16_t * {
-    t = min(t, T - 1);
-    return t < P ? vc + int64_t(t) * a.cs[1] : vs + int64_t(t - P) * a.ks[1];
-  };
-  auto load_k = [&](int jb, bf16x8 (&kf)[KK]) {
-    const uint16_t *p = krow(32 * jb + lq) + 8 * hf;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) kf[kk] = *reinterpret_cast<const bf16x8 *>(p + 16 * kk);
-  };
-  // V block: load i covers rows 4*i*(16/VCOL).. ; lane -> (row, 16-byte column)
   constexpr int VCOL = D / 8;          // 16-byte columns per row
   constexpr int RPL = 64 / VCOL;       // rows covered by one wave-wide load
   const int vcol = lane % VCOL, vr0 = lane / VCOL;
-  u32x4 vreg[VL];
-  auto load_v = [&](int jb) {
+  u32x4 kreg[VL], vreg[VL];
+  auto load_kv = [&](int jb) {
 #pragma unroll
-    for (int i = 0; i < VL; ++i)
-      vreg[i] = *reinterpret_cast<const u32x4 *>(vrow(32 * jb + RPL * i + vr0) + 8 * vcol);
+    for (int i = 0; i < VL; ++i) {
+      const int t = 32 * jb + RPL * i + vr0;
+      kreg[i] = *reinterpret_cast<const u32x4 *>(row_ptr(kc, ks, t) + 8 * vcol);
+      vreg[i] = *reinterpret_cast<const u32x4 *>(row_ptr(vc, vs, t) + 8 * vcol);
+    }
   };
-  auto stage_v = [&](int jb) {
+  auto stage_kv = [&](int jb) {
 #pragma unroll
     for (int i = 0; i < VL; ++i) {
       const int r = RPL * i + vr0;
       u32x4 v = vreg[i];
       if (32 * jb + r >= T) v = u32x4{0, 0, 0, 0};  // keys beyond T contribute exact zeros
-      *reinterpret_cast<u32x4 *>(wlds + r * G::VPITCH + 16 * vcol) = v;
+      *reinterpret_cast<u32x4 *>(wlds + r * G::KPITCH + 16 * vcol) = kreg[i];
+      *reinterpret_cast<u32x4 *>(wlds + G::KBYTES + r * G::VPITCH + 16 * vcol) = v;
     }
   };
 
-  bf16x8 kf[KK];
   auto block = [&](int jb) {
-    stage_v(jb);
+    stage_kv(jb);
     const int jn = jb + WK;
-    if (jn < NB) load_v(jn);
-    // S^T block
+    if (jn < NB) load_kv(jn);  // in flight while this block is worked on
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
-    // the K registers are free again: fetch the next block's rows while this
-    // block goes through the soft-max and the second product
-    if (jn < NB) load_k(jn, kf);
-    softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, wlds);
+    for (int kk = 0; kk < KK; ++kk) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(wlds + lq * G::KPITCH + (16 * kk + 8 * hf) * 2);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+    }
+    softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, wlds + G::KBYTES);
   };
 
-  if (wk < NB) {
-    load_k(wk, kf);
-    load_v(wk);
-  }
+  if (wk < NB) load_kv(wk);
   for (int jb = wk; jb < NB; jb += WK) block(jb);
-
   merge_store<D, WM, WK>(a, oacc, mref, lsum, smem, b, h, q0, N);
 }
 
