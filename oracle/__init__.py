@@ -131,3 +131,35 @@ def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
                              _p(out["commit_len"]), _p(out["status_flags"]), _p(out["tau_used"]))
     assert rc == 0, rc
     return out
+
+
+def select_scattered(margin, suffix_len, count):
+    """Scattered-Margin selection: per sequence the count[b] active positions with
+    the largest margins (ties: lower position).  Returns (sel_index int32 [B,S],
+    ascending, padded with -1; sel_mask uint8 [B,S])."""
+    B, S = margin.shape
+    assert margin.dtype == torch.float32
+    sl, ct = _i32(suffix_len), _i32(count)
+    idx = torch.empty((B, S), dtype=torch.int32)
+    mask = torch.empty((B, S), dtype=torch.uint8)
+    rc = lib().oracle_select_scattered(B, S, _p(margin), _p(sl), _p(ct), _p(idx), _p(mask))
+    assert rc == 0
+    return idx, mask
+
+
+def gather_append(sel_index, count, prefix_len, k_suf, v_suf, k_cache, v_cache):
+    """Cache rows [P_b, P_b+k_b) <- suffix rows sel_index[b, :k_b] for every layer.
+    Mutates the caches and prefix_len IN PLACE."""
+    layers = len(k_suf)
+    B, S, Hkv, D = k_suf[0].shape
+    C = k_cache[0].shape[1]
+    PtrArr = ctypes.c_void_p * layers
+    arrs = [PtrArr(*[t.data_ptr() for t in lst]) for lst in (k_suf, v_suf, k_cache, v_cache)]
+    for lst in (k_suf, v_suf, k_cache, v_cache):
+        for t in lst:
+            assert t.is_contiguous() and t.device.type == "cpu"
+    assert sel_index.dtype == torch.int32 and prefix_len.dtype == torch.int32
+    ct = _i32(count)
+    rc = lib().oracle_gather_append(_dt(k_suf[0]), B, S, Hkv, D, C, layers, _p(sel_index), _p(ct),
+                                    arrs[0], arrs[1], arrs[2], arrs[3], _p(prefix_len))
+    assert rc == 0

@@ -16,6 +16,9 @@
  *                        suffix's own K/V (Section 3.2, approximate KV caching).
  *   oracle_confidence  - top-1 id and logit margin of Eq. 1 (Algorithm 1
  *                        line 5), plus the top-1 soft-max probability.
+ *   oracle_select_scattered, oracle_gather_append - the Scattered-Margin
+ *                        baseline of Section 4.3.3 (same block size, scattered
+ *                        positions) and the cache update it implies.
  *   oracle_commit      - L'(tau) of Section 3.2 (longest all-stable run from
  *                        the left), the boundary snap and L_min / fallback of
  *                        the unnumbered snap equation and Algorithm 1 lines
@@ -297,6 +300,71 @@ int oracle_commit(int kv_dtype, int B, int S, int V, int Hkv, int D, int C, int 
             }
         prefix_len[b] = P + L;
         suffix_len[b] = N - L;
+    }
+    return 0;
+}
+
+/*
+ * Scattered-Margin selection (Section 4.3.3, the baseline that keeps LSP's block
+ * size but drops its topology): of the N_b active positions of sequence b, the
+ * count[b] positions with the largest margins, wherever they are; among equal
+ * margins the lower position wins.  sel_index[b, 0..k) lists them in ascending
+ * position order (entries beyond k are -1), sel_mask[b, i] = 1 for a selected
+ * position.  k = min(count[b], N_b), not below 0.
+ */
+int oracle_select_scattered(int B, int S, const float *margin, const int32_t *suffix_len,
+                            const int32_t *count, int32_t *sel_index, uint8_t *sel_mask)
+{
+    for (int b = 0; b < B; ++b) {
+        int N = suffix_len[b];
+        int k = count[b] < N ? count[b] : N;
+        if (k < 0) k = 0;
+        const float *mg = margin + (int64_t)b * S;
+        uint8_t *mk = sel_mask + (int64_t)b * S;
+        int32_t *ix = sel_index + (int64_t)b * S;
+        for (int i = 0; i < S; ++i) { mk[i] = 0; ix[i] = -1; }
+        for (int r = 0; r < k; ++r) {          /* pick the best remaining position k times */
+            int best = -1;
+            for (int i = 0; i < N; ++i)
+                if (!mk[i] && (best < 0 || mg[i] > mg[best])) best = i;
+            mk[best] = 1;
+        }
+        int n = 0;
+        for (int i = 0; i < N; ++i)
+            if (mk[i]) ix[n++] = i;
+    }
+    return 0;
+}
+
+/*
+ * Gathered append: what the cache update becomes when the committed positions
+ * are scattered.  For every layer, cache rows [P_b, P_b + k_b) receive the suffix
+ * rows sel_index[b, 0..k_b) in that order (K and V), k_b = count[b] cut to the
+ * cache room C - P_b; prefix_len[b] += k_b.  (suffix_len is left alone: with
+ * scattered commits the remaining active positions are no longer a suffix.)
+ */
+int oracle_gather_append(int kv_dtype, int B, int S, int Hkv, int D, int C, int layers,
+                         const int32_t *sel_index, const int32_t *count,
+                         const void *const *k_suf, const void *const *v_suf,
+                         void *const *k_cache, void *const *v_cache, int32_t *prefix_len)
+{
+    size_t esz = kv_dtype == 0 ? 4 : 2;
+    size_t row = (size_t)Hkv * D * esz;
+    for (int b = 0; b < B; ++b) {
+        int P = prefix_len[b];
+        int k = count[b];
+        if (k > C - P) k = C - P > 0 ? C - P : 0;
+        if (k < 0) k = 0;
+        for (int j = 0; j < k; ++j) {
+            int src = sel_index[(int64_t)b * S + j];
+            for (int l = 0; l < layers; ++l) {
+                memcpy((char *)k_cache[l] + ((size_t)b * C + P + j) * row,
+                       (const char *)k_suf[l] + ((size_t)b * S + src) * row, row);
+                memcpy((char *)v_cache[l] + ((size_t)b * C + P + j) * row,
+                       (const char *)v_suf[l] + ((size_t)b * S + src) * row, row);
+            }
+        }
+        prefix_len[b] = P + k;
     }
     return 0;
 }
