@@ -201,6 +201,52 @@ int32_t lsp_commit(const lsp_commit_desc *desc, const float *margin, const int32
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------- *
+ * Scattered-Margin baseline (Section 4.3.3: LSP's block size, but the most
+ * confident positions from anywhere in the active sequence) - the pieces
+ * needed to MEASURE what the prefix-first topology saves.
+ * ------------------------------------------------------------------------- */
+
+/*
+ * Per sequence b: the k = min(count[b], N_b) active positions with the largest
+ * margins; equal margins are taken in position order.  sel_index[b, 0..k)
+ * lists them ascending, the rest of the row is -1; sel_mask[b, i] = 1 for a
+ * selected position (0 elsewhere, inactive positions included).
+ * margin: device fp32 [B,S]; suffix_len, count: device int32[B]; sel_index:
+ * device int32 [B,S]; sel_mask: device uint8 [B,S].  S <= 8192.
+ */
+int32_t lsp_select_scattered(const float *margin, int32_t B, int32_t S, const int32_t *suffix_len,
+                             const int32_t *count, int32_t *sel_index, uint8_t *sel_mask,
+                             void *stream);
+
+/*
+ * Gathered append: for every layer, cache rows [P_b, P_b + k_b) receive the
+ * suffix rows sel_index[b, 0..k_b) in that order (K and V), with k_b = count[b]
+ * cut to the cache room C - P_b; then prefix_len[b] += k_b and appended[b] = k_b
+ * (appended may be NULL).  suffix_len is not touched: after a scattered commit
+ * the remaining positions are no longer a suffix.  Layouts, alignment and the
+ * HOST pointer tables as for lsp_commit; strides in elements, 0 = dense.
+ * Indices outside [0,S) are clamped into the buffer.
+ */
+int32_t lsp_kv_gather_append(int32_t kv_dtype, int32_t B, int32_t S, int32_t Hkv, int32_t D, int32_t C,
+                             int32_t num_layers, int64_t suf_batch_stride, int64_t cache_batch_stride,
+                             const int32_t *sel_index, const int32_t *count,
+                             const void *const *k_suf_layers, const void *const *v_suf_layers,
+                             void *const *k_cache_layers, void *const *v_cache_layers,
+                             int32_t *prefix_len, int32_t *appended, void *stream);
+
+/*
+ * lsp_attn_step over a cache that is addressed through a row index, as a cache
+ * fragmented by scattered commits is: key t < P_b of sequence b is cache row
+ * cache_row_index[b*C + t] (device int32 [B,C]; values outside [0,C) are
+ * clamped into the buffer).  Everything else as lsp_attn_step.
+ */
+int32_t lsp_attn_step_gather(const lsp_attn_desc *desc, const void *q, const void *k_suf,
+                             const void *v_suf, const void *k_cache, const void *v_cache,
+                             const int32_t *cache_row_index, const int32_t *prefix_len,
+                             const int32_t *suffix_len, void *out, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- *
  * Flip bookkeeping for a decode loop (Section 4.3.4: share of active-suffix
  * positions whose top-1 prediction changes between consecutive steps).
  *

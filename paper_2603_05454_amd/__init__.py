@@ -45,7 +45,8 @@ class CommitDesc(ctypes.Structure):
 
 EXPORTS = ["lsp_version", "lsp_last_error", "lsp_attn_workspace_bytes", "lsp_attn_step",
            "lsp_confidence_workspace_bytes", "lsp_confidence", "lsp_commit_workspace_bytes",
-           "lsp_commit", "lsp_flip_update"]
+           "lsp_commit", "lsp_flip_update", "lsp_select_scattered", "lsp_kv_gather_append",
+           "lsp_attn_step_gather"]
 
 
 def lib() -> ctypes.CDLL:
@@ -60,7 +61,8 @@ def lib() -> ctypes.CDLL:
         L.lsp_last_error.restype = ctypes.c_char_p
         for n in ("lsp_attn_workspace_bytes", "lsp_confidence_workspace_bytes", "lsp_commit_workspace_bytes"):
             getattr(L, n).restype = ctypes.c_size_t
-        for n in ("lsp_attn_step", "lsp_confidence", "lsp_commit", "lsp_flip_update"):
+        for n in ("lsp_attn_step", "lsp_confidence", "lsp_commit", "lsp_flip_update", "lsp_select_scattered",
+                  "lsp_kv_gather_append", "lsp_attn_step_gather"):
             getattr(L, n).restype = ctypes.c_int32
         _lib = L
     return _lib
@@ -108,11 +110,12 @@ def attn_workspace_bytes(dtype, B, S, Hq, Hkv, D, C) -> int:
 
 
 def attn_step(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len, scale=0.0, out=None,
-              workspace=None):
+              workspace=None, cache_row_index=None):
     """lsp_attn_step: q [B,S,Hq,D], k_suf/v_suf [B,S,Hkv,D], caches [B,C,Hkv,D],
     prefix_len/suffix_len int32 [B].  Returns out [B,S,Hq,D] (same dtype as q);
-    rows >= suffix_len[b] are not written."""
-    _dev(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len)
+    rows >= suffix_len[b] are not written.  cache_row_index int32 [B,C] selects
+    lsp_attn_step_gather (key t of the prefix is cache row cache_row_index[b,t])."""
+    _dev(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len, cache_row_index)
     B, S, Hq, D = q.shape
     if out is None:
         out = torch.empty((B, S, Hq, D), dtype=q.dtype, device=q.device)
@@ -127,9 +130,17 @@ def attn_step(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len, scale=0
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    rc = lib().lsp_attn_step(ctypes.byref(d), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_cache),
-                             _ptr(v_cache), _ptr(prefix_len), _ptr(suffix_len), _ptr(out),
-                             _ptr(workspace), ctypes.c_size_t(wb), _stream())
+    if cache_row_index is None:
+        rc = lib().lsp_attn_step(ctypes.byref(d), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_cache),
+                                 _ptr(v_cache), _ptr(prefix_len), _ptr(suffix_len), _ptr(out),
+                                 _ptr(workspace), ctypes.c_size_t(wb), _stream())
+    else:
+        assert cache_row_index.dtype == torch.int32 and cache_row_index.is_contiguous()
+        assert tuple(cache_row_index.shape) == (B, k_cache.shape[1])
+        rc = lib().lsp_attn_step_gather(ctypes.byref(d), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_cache),
+                                        _ptr(v_cache), _ptr(cache_row_index), _ptr(prefix_len),
+                                        _ptr(suffix_len), _ptr(out), _ptr(workspace), ctypes.c_size_t(wb),
+                                        _stream())
     _check(rc, "lsp_attn_step")
     return out
 
@@ -224,3 +235,34 @@ def flip_update(top1_id, prefix_len, suffix_len, base_prefix_len, last_id, count
     rc = lib().lsp_flip_update(_ptr(top1_id), B, S, last_id.shape[1], _ptr(prefix_len), _ptr(suffix_len),
                                _ptr(base_prefix_len), _ptr(last_id), _ptr(counters), _stream())
     _check(rc, "lsp_flip_update")
+
+
+def select_scattered(margin, suffix_len, count, out=None):
+    """lsp_select_scattered: the count[b] highest-margin active positions of every
+    sequence.  Returns (sel_index int32 [B,S] ascending, -1 padded; sel_mask uint8 [B,S])."""
+    _dev(margin, suffix_len, count)
+    B, S = margin.shape
+    if out is None:
+        out = (torch.empty((B, S), dtype=torch.int32, device=margin.device),
+               torch.empty((B, S), dtype=torch.uint8, device=margin.device))
+    rc = lib().lsp_select_scattered(_ptr(margin), B, S, _ptr(suffix_len), _ptr(count), _ptr(out[0]),
+                                    _ptr(out[1]), _stream())
+    _check(rc, "lsp_select_scattered")
+    return out
+
+
+def kv_gather_append(sel_index, count, prefix_len, layers: LayerTable, appended=None):
+    """lsp_kv_gather_append: cache rows [P_b, P_b+k_b) <- suffix rows sel_index[b, :k_b]
+    for every layer of `layers`; prefix_len advanced in place.  Returns appended int32 [B]."""
+    _dev(sel_index, count, prefix_len, appended)
+    B, S = sel_index.shape
+    assert S == layers.S
+    if appended is None:
+        appended = torch.empty(B, dtype=torch.int32, device=sel_index.device)
+    a = layers.arrays
+    rc = lib().lsp_kv_gather_append(layers.kv_dtype, B, S, layers.Hkv, layers.D, layers.C, layers.n,
+                                    ctypes.c_int64(layers.suf_bs), ctypes.c_int64(layers.cache_bs),
+                                    _ptr(sel_index), _ptr(count), a[0], a[1], a[2], a[3], _ptr(prefix_len),
+                                    _ptr(appended), _stream())
+    _check(rc, "lsp_kv_gather_append")
+    return appended

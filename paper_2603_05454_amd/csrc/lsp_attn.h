@@ -13,7 +13,16 @@ struct AttnArgs {
   int64_t qs[3], ks[3], cs[3], os[3];  // element strides: batch, row, head
   void *workspace;
   int32_t unit_group;  // set by the bf16 launcher: units per placement group
+  const int32_t *cache_rows;  // gather form only: key t < P_b of sequence b is cache row cache_rows[b*C + t]; else null
 };
+
+// Cache row that holds key t (t < P_b) of sequence b.
+template <bool GATHER>
+__device__ __forceinline__ int cache_row(const AttnArgs &a, int b, int t) {
+  if (!GATHER) return t;
+  const int r = a.cache_rows[int64_t(b) * a.C + t];
+  return min(max(r, 0), a.C - 1);  // a bad index must not leave the buffer
+}
 
 int32_t launch_attn_f32(const AttnArgs &a, hipStream_t st);
 int32_t launch_attn_bf16(const AttnArgs &a, hipStream_t st);

@@ -47,11 +47,12 @@ extern "C" size_t lsp_attn_workspace_bytes(const lsp_attn_desc *d) {
   return lsp::attn_bf16_workspace_bytes(d->B, d->S, d->Hq, d->D);
 }
 
-extern "C" int32_t lsp_attn_step(const lsp_attn_desc *d, const void *q, const void *k_suf,
-                                 const void *v_suf, const void *k_cache, const void *v_cache,
-                                 const int32_t *prefix_len, const int32_t *suffix_len, void *out,
-                                 void *workspace, size_t workspace_bytes, void *stream) {
-  using namespace lsp;
+namespace lsp {
+namespace {
+int32_t attn_entry(const lsp_attn_desc *d, const void *q, const void *k_suf, const void *v_suf,
+                   const void *k_cache, const void *v_cache, const int32_t *cache_rows,
+                   const int32_t *prefix_len, const int32_t *suffix_len, void *out, void *workspace,
+                   size_t workspace_bytes, void *stream) {
   AttnArgs a;
   const int32_t rc = check(d, a);
   if (rc != LSP_OK) return rc;
@@ -68,6 +69,28 @@ extern "C" int32_t lsp_attn_step(const lsp_attn_desc *d, const void *q, const vo
   }
   a.q = q; a.k_suf = k_suf; a.v_suf = v_suf; a.k_cache = k_cache; a.v_cache = v_cache; a.out = out;
   a.prefix_len = prefix_len; a.suffix_len = suffix_len; a.workspace = workspace;
+  a.cache_rows = cache_rows;
+  a.unit_group = 1;
   hipStream_t st = static_cast<hipStream_t>(stream);
   return d->dtype == LSP_F32 ? launch_attn_f32(a, st) : launch_attn_bf16(a, st);
+}
+}  // namespace
+}  // namespace lsp
+
+extern "C" int32_t lsp_attn_step(const lsp_attn_desc *d, const void *q, const void *k_suf,
+                                 const void *v_suf, const void *k_cache, const void *v_cache,
+                                 const int32_t *prefix_len, const int32_t *suffix_len, void *out,
+                                 void *workspace, size_t workspace_bytes, void *stream) {
+  return lsp::attn_entry(d, q, k_suf, v_suf, k_cache, v_cache, nullptr, prefix_len, suffix_len, out,
+                         workspace, workspace_bytes, stream);
+}
+
+extern "C" int32_t lsp_attn_step_gather(const lsp_attn_desc *d, const void *q, const void *k_suf,
+                                        const void *v_suf, const void *k_cache, const void *v_cache,
+                                        const int32_t *cache_row_index, const int32_t *prefix_len,
+                                        const int32_t *suffix_len, void *out, void *workspace,
+                                        size_t workspace_bytes, void *stream) {
+  LSP_CHECK_ARG(cache_row_index != nullptr, "lsp_attn_step_gather: null row index");
+  return lsp::attn_entry(d, q, k_suf, v_suf, k_cache, v_cache, cache_row_index, prefix_len, suffix_len,
+                         out, workspace, workspace_bytes, stream);
 }

@@ -280,7 +280,7 @@ __device__ __forceinline__ void merge_store(const AttnArgs &a, const f32x16 (&oa
   }
 }
 
-template <int D, int WM, int WK>
+template <int D, int WM, int WK, bool GATHER>
 __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) {
   using G = Geo<D>;
   constexpr int KK = D / 16;  // d-steps of the first product
@@ -329,7 +329,7 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
   // for 32 bytes each, and at small sizes those cycles are the critical path.)
   auto row_ptr = [&](const uint16_t *cache, const uint16_t *suf, int t) -> const uint16_t * {
     t = min(t, T - 1);
-    return t < P ? cache + int64_t(t) * a.cs[1] : suf + int64_t(t - P) * a.ks[1];
+    return t < P ? cache + int64_t(cache_row<GATHER>(a, b, t)) * a.cs[1] : suf + int64_t(t - P) * a.ks[1];
   };
   constexpr int VCOL = D / 8;          // 16-byte columns per row
   constexpr int RPL = 64 / VCOL;       // rows covered by one wave-wide load
@@ -374,8 +374,8 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
   merge_store<D, WM, WK>(a, oacc, mref, lsum, smem, b, h, q0, N);
 }
 
-template <int D, int WM, int WK>
-int32_t launch(AttnArgs a, hipStream_t st) {
+template <int D, int WM, int WK, bool GATHER>
+int32_t launch_g(AttnArgs a, hipStream_t st) {
   const int64_t nwg = place_grid(a, 32 * WM);
   if (nwg > 0x7fffffff) {
     set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
@@ -383,7 +383,7 @@ int32_t launch(AttnArgs a, hipStream_t st) {
   }
   const dim3 grid(static_cast<unsigned>(nwg), 1, 1);
   const size_t lds = size_t(WM * WK) * Geo<D>::WAVE_LDS;
-  auto kern = attn_bf16_kernel<D, WM, WK>;
+  auto kern = attn_bf16_kernel<D, WM, WK, GATHER>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -405,7 +405,7 @@ struct TileGeo {
   static constexpr int STAGE = KBYTES + 32 * VPITCH;
 };
 
-template <int D, int WM, int OCC, int PD>
+template <int D, int WM, int OCC, int PD, bool GATHER>
 __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a) {
   using TG = TileGeo<D>;
   constexpr int NT = 64 * WM;
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
     for (int i = 0; i < PIECES; ++i) {
       const int pc = tid + NT * i;
       const int t = min(32 * jb + pc / CPR, T - 1);
-      const int64_t off = t < P ? int64_t(t) * a.cs[1] : int64_t(t - P) * a.ks[1];
+      const int64_t off = t < P ? int64_t(cache_row<GATHER>(a, b, t)) * a.cs[1] : int64_t(t - P) * a.ks[1];
       const uint16_t *kp = (t < P ? kc : ks) + off + 8 * (pc % CPR);
       const uint16_t *vp = (t < P ? vc : vs) + off + 8 * (pc % CPR);
       kr[i] = *reinterpret_cast<const u32x4 *>(kp);
@@ -523,15 +523,15 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
   }
 }
 
-template <int D, int WM, int OCC, int PD>
-int32_t launch_tile(AttnArgs a, hipStream_t st) {
+template <int D, int WM, int OCC, int PD, bool GATHER>
+int32_t launch_tile_g(AttnArgs a, hipStream_t st) {
   const int64_t nwg = place_grid(a, 32 * WM);
   if (nwg > 0x7fffffff) {
     set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
     return LSP_ERR_UNSUPPORTED;
   }
   const size_t lds = 2 * size_t(TileGeo<D>::STAGE);
-  auto kern = attn_bf16_tile_kernel<D, WM, OCC, PD>;
+  auto kern = attn_bf16_tile_kernel<D, WM, OCC, PD, GATHER>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -542,6 +542,16 @@ int32_t launch_tile(AttnArgs a, hipStream_t st) {
   kern<<<dim3(static_cast<unsigned>(nwg), 1, 1), 64 * WM, lds, st>>>(a);
   LSP_CHECK_LAUNCH("lsp_attn_step: bf16 tile launch");
   return LSP_OK;
+}
+
+// contiguous cache, or rows through an index (Scattered-Margin measurement)
+template <int D, int WM, int WK>
+int32_t launch(const AttnArgs &a, hipStream_t st) {
+  return a.cache_rows ? launch_g<D, WM, WK, true>(a, st) : launch_g<D, WM, WK, false>(a, st);
+}
+template <int D, int WM, int OCC, int PD>
+int32_t launch_tile(const AttnArgs &a, hipStream_t st) {
+  return a.cache_rows ? launch_tile_g<D, WM, OCC, PD, true>(a, st) : launch_tile_g<D, WM, OCC, PD, false>(a, st);
 }
 
 template <int D>

@@ -48,8 +48,9 @@ __global__ __launch_bounds__(kQ) void attn_f32_kernel(AttnArgs a) {
     for (int e = tid; e < nt * (D / 4); e += kQ) {
       const int r = e / (D / 4), c = (e % (D / 4)) * 4;
       const int t = t0 + r;
-      const float *kp = t < P ? kc + int64_t(t) * a.cs[1] : ks + int64_t(t - P) * a.ks[1];
-      const float *vp = t < P ? vc + int64_t(t) * a.cs[1] : vs + int64_t(t - P) * a.ks[1];
+      const int64_t crow = t < P ? (a.cache_rows ? cache_row<true>(a, b, t) : t) : 0;
+      const float *kp = t < P ? kc + crow * a.cs[1] : ks + int64_t(t - P) * a.ks[1];
+      const float *vp = t < P ? vc + crow * a.cs[1] : vs + int64_t(t - P) * a.ks[1];
       *reinterpret_cast<float4 *>(&sK[r][c]) = *reinterpret_cast<const float4 *>(kp + c);
       *reinterpret_cast<float4 *>(&sV[r][c]) = *reinterpret_cast<const float4 *>(vp + c);
     }
