@@ -47,7 +47,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "scatter"],
+                    help="c1..c4: one step; c5: the decode loop; scatter: prefix-first against Scattered-Margin commits")
     ap.add_argument("--sizing", default="tau", choices=["tau", "adaptive", "full"],
                     help="c5: fixed threshold (default), adaptive threshold (Eq. 2, [0.25, 0.5]) or the Full baseline (1 position per step)")
     ap.add_argument("--loop-steps", type=int, default=0, help="c5: stop the decode loop after this many steps (0 = run to the end)")
@@ -329,6 +330,80 @@ def run_loop_workload(max_steps=0, sizing="tau"):
     return r["committed"] / lsp_s, r["lsp_ms"] / max(1, r["steps"]), config
 
 
+def run_scatter_comparison(layers=32):
+    """Prefix-first against Scattered-Margin on the config-4 shapes (Section 4.3.3's systems
+    claim, measured): the same number of rows per sequence is committed either as LSP's
+    contiguous block or at the highest-margin positions anywhere; the cache is then either
+    contiguous or addressed through a row index (a random permutation: full fragmentation)."""
+    import torch
+    import paper_2603_05454_amd as lsp
+    import workloads as W
+
+    dev = torch.device("cuda:0")
+    w = W.scaled(W.C4, layers=layers)
+    es = W.elem_bytes(w)
+    _, bitmap = W.make_delimiters(w)
+    bitmap = bitmap.to(dev)
+    z, _ = W.make_logits(w, device=dev)
+    kv = [W.make_layer_kv(w, l, device=dev) for l in range(w.layers)]
+    table = lsp.LayerTable([L["k_suf"] for L in kv], [L["v_suf"] for L in kv], [L["k_cache"] for L in kv], [L["v_cache"] for L in kv])
+    pl0, sl0 = W.make_lengths(w, device=dev)
+    ids, prob, margin = lsp.confidence(z)
+    pl, sl = pl0.clone(), sl0.clone()
+    out = lsp.commit(margin, ids, bitmap, w.V, w.tau, w.window, w.min_commit, 1, pl, sl, C=w.C)   # sizes only
+    count = out["commit_len"].clone()
+    rows_total = int(count.sum().item())
+    sel = lsp.select_scattered(margin, sl0, count)
+    appended = torch.empty(w.B, dtype=torch.int32, device=dev)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    perm = torch.stack([torch.randperm(w.C, generator=g) for _ in range(w.B)]).to(torch.int32).to(dev)
+    attn_out = torch.empty_like(kv[0]["q"])
+
+    def timed(fn, reps=30):
+        for _ in range(15):      # clocks ramp for some milliseconds after idle
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / reps
+
+    def reset():
+        pl.copy_(pl0)
+        sl.copy_(sl0)
+
+    def contiguous_commit():
+        reset()
+        lsp.commit(margin, ids, bitmap, w.V, w.tau, w.window, w.min_commit, 1, pl, sl, layers=table, out=out)
+
+    def scattered_commit():
+        reset()
+        lsp.select_scattered(margin, sl, count, out=sel)
+        lsp.kv_gather_append(sel[0], count, pl, table, appended=appended)
+
+    L0 = kv[0]
+    t_reset = timed(reset)
+    t_cont = timed(contiguous_commit) - t_reset
+    t_scat = timed(scattered_commit) - t_reset
+    t_sel = timed(lambda: lsp.select_scattered(margin, sl0, count, out=sel))
+    t_attn = timed(lambda: lsp.attn_step(L0["q"], L0["k_suf"], L0["v_suf"], L0["k_cache"], L0["v_cache"], pl0, sl0, out=attn_out))
+    t_attn_g = timed(lambda: lsp.attn_step(L0["q"], L0["k_suf"], L0["v_suf"], L0["k_cache"], L0["v_cache"], pl0, sl0,
+                                           out=attn_out, cache_row_index=perm))
+    moved = 2 * rows_total * w.Hkv * w.D * es * 2 * w.layers
+    fl = W.attn_flops(w)
+    return {"workload": "c4 shapes, %d layers" % w.layers, "rows_committed_per_step": rows_total,
+            "commit_prefix_first_us": round(t_cont * 1e6, 1), "commit_scattered_us": round(t_scat * 1e6, 1),
+            "of_which_selection_us": round(t_sel * 1e6, 1),
+            "append_prefix_first_GBs": round(moved / t_cont / 1e9, 1), "append_scattered_GBs": round(moved / t_scat / 1e9, 1),
+            "attention_contiguous_us": round(t_attn * 1e6, 1), "attention_indexed_us": round(t_attn_g * 1e6, 1),
+            "attention_contiguous_TFLOPs": round(fl / t_attn / 1e12, 1), "attention_indexed_TFLOPs": round(fl / t_attn_g / 1e12, 1),
+            "commit_ratio_scattered_over_prefix": round(t_scat / t_cont, 3),
+            "attention_ratio_indexed_over_contiguous": round(t_attn_g / t_attn, 3)}
+
+
 def calibrate_copy():
     """A plain device-to-device copy of known size (1 GiB read + 1 GiB written per
     launch, 5 launches): what rocprofv3's FETCH_SIZE / WRITE_SIZE counters read
@@ -357,6 +432,10 @@ def main():
         calibrate_copy()
         return
     K, Wm = args.steps, args.warmup
+    if args.workload == "scatter":
+        print(json.dumps({"comparison": "prefix-first vs Scattered-Margin (Section 4.3.3)", "n_gpus": 1, "dtype": "bf16",
+                          "data": "synthetic", **run_scatter_comparison(args.layers or 32)}))
+        return
     if args.workload == "c5":
         value, ms, config = run_loop_workload(args.loop_steps, args.sizing)
         print(json.dumps({"metric": "committed tokens/sec + per-step latency (ms), LLaDA-8B shape, 1 MI355X",

@@ -4,12 +4,11 @@
 // saves: selection, a gathered append, and (in lsp_attn.hip) attention over a
 // cache addressed through a row index.
 //
-// Selection: one workgroup per sequence.  The margins of the active positions
-// are copied to LDS; every thread ranks its positions by counting
+// Selection: every position is ranked by counting
 // (rank_i = #{j : m_j > m_i} + #{j < i : m_j = m_i}, so equal margins are
-// ordered by position) and a position is selected when its rank is below the
-// requested count.  The selected positions are then written in ascending order:
-// wave ballots give the in-wave offsets, an LDS prefix over the waves the rest.
+// ordered by position) against the sequence's margins held in LDS, and is
+// selected when its rank is below the requested count; a second kernel writes
+// the selected positions in ascending order.
 #include "lsp_common.h"
 
 namespace lsp {
@@ -20,36 +19,61 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kSelThreads = 256;
 constexpr int kSelMaxS = 8192;  // margins of one sequence live in LDS
 
-__global__ __launch_bounds__(kSelThreads) void select_kernel(
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// grid (ceil(S / 256), B): every workgroup ranks 256 positions of one sequence
+// against all of its active margins (copied to LDS, padded with -inf to a
+// multiple of 4 so that the scan reads 16 bytes per LDS broadcast).
+__global__ __launch_bounds__(kSelThreads) void rank_kernel(
     const float *__restrict__ margin, int S, const int32_t *__restrict__ suffix_len,
-    const int32_t *__restrict__ count, int32_t *__restrict__ sel_index,
-    uint8_t *__restrict__ sel_mask) {
-  extern __shared__ float s_m[];
+    const int32_t *__restrict__ count, uint8_t *__restrict__ sel_mask) {
+  extern __shared__ __attribute__((aligned(16))) float s_m[];
+  const int b = blockIdx.y, tid = threadIdx.x;
+  const int N = min(max(suffix_len[b], 0), S);
+  const int k = min(max(count[b], 0), N);
+  const float *mg = margin + int64_t(b) * S;
+  const int i = blockIdx.x * kSelThreads + tid;
+  if (k == 0 || blockIdx.x * kSelThreads >= N) {  // uniform: nothing to rank here
+    if (i < S) sel_mask[int64_t(b) * S + i] = 0;
+    return;
+  }
+  const int N4 = (N + 3) & ~3;
+  for (int j = tid; j < N4; j += kSelThreads) s_m[j] = j < N ? mg[j] : -INFINITY;
+  __syncthreads();
+  bool sel = false;
+  if (i < N) {
+    const float mi = s_m[i];
+    int rank = 0;
+    for (int j = 0; j < N4; j += 4) {
+      const f32x4 m = *reinterpret_cast<const f32x4 *>(s_m + j);
+      rank += (m.x > mi) || (m.x == mi && j < i);
+      rank += (m.y > mi) || (m.y == mi && j + 1 < i);
+      rank += (m.z > mi) || (m.z == mi && j + 2 < i);
+      rank += (m.w > mi) || (m.w == mi && j + 3 < i);
+    }
+    sel = rank < k;
+  }
+  if (i < S) sel_mask[int64_t(b) * S + i] = sel ? 1 : 0;
+}
+
+// One workgroup per sequence writes the selected positions in ascending order:
+// wave ballots give the in-wave offsets, an LDS prefix over the waves the rest.
+__global__ __launch_bounds__(kSelThreads) void compact_kernel(
+    int S, const int32_t *__restrict__ suffix_len, const int32_t *__restrict__ count,
+    const uint8_t *__restrict__ sel_mask, int32_t *__restrict__ sel_index) {
   __shared__ int s_wave[kSelThreads / kWave];
   __shared__ int s_base;
   const int b = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & (kWave - 1), wave = tid / kWave;
   const int N = min(max(suffix_len[b], 0), S);
   const int k = min(max(count[b], 0), N);
-  const float *mg = margin + int64_t(b) * S;
   int32_t *ix = sel_index + int64_t(b) * S;
-  uint8_t *mk = sel_mask + int64_t(b) * S;
-  for (int i = tid; i < N; i += kSelThreads) s_m[i] = mg[i];
+  const uint8_t *mk = sel_mask + int64_t(b) * S;
   if (tid == 0) s_base = 0;
   __syncthreads();
-  for (int base = 0; base < S; base += kSelThreads) {
+  for (int base = 0; base < N; base += kSelThreads) {
     const int i = base + tid;
-    bool sel = false;
-    if (i < N && k > 0) {
-      const float mi = s_m[i];
-      int rank = 0;
-      for (int j = 0; j < N; ++j) {  // every lane reads the same word: an LDS broadcast
-        const float mj = s_m[j];
-        rank += (mj > mi) || (mj == mi && j < i);
-      }
-      sel = rank < k;
-    }
-    if (i < S) mk[i] = sel ? 1 : 0;
+    const bool sel = i < N && mk[i] != 0;
     const unsigned long long bal = __ballot(sel);
     if (lane == 0) s_wave[wave] = __popcll(bal);
     __syncthreads();
@@ -117,9 +141,13 @@ extern "C" int32_t lsp_select_scattered(const float *margin, int32_t B, int32_t 
     set_error("lsp_select_scattered: S = %d exceeds the %d positions one workgroup ranks", S, kSelMaxS);
     return LSP_ERR_UNSUPPORTED;
   }
-  select_kernel<<<B, kSelThreads, size_t(S) * sizeof(float), static_cast<hipStream_t>(stream)>>>(
-      margin, S, suffix_len, count, sel_index, sel_mask);
-  LSP_CHECK_LAUNCH("lsp_select_scattered: launch");
+  LSP_CHECK_ARG(B <= 65535, "lsp_select_scattered: B must be <= 65535");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  rank_kernel<<<dim3((S + kSelThreads - 1) / kSelThreads, B), kSelThreads, size_t(S + 4) * sizeof(float), st>>>(
+      margin, S, suffix_len, count, sel_mask);
+  LSP_CHECK_LAUNCH("lsp_select_scattered: rank launch");
+  compact_kernel<<<B, kSelThreads, 0, st>>>(S, suffix_len, count, sel_mask, sel_index);
+  LSP_CHECK_LAUNCH("lsp_select_scattered: compact launch");
   return LSP_OK;
 }
 
