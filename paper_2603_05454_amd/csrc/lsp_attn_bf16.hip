@@ -450,11 +450,45 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
   // PD register sets hold the blocks in flight: the loop is throughput-bound by
   // bytes in flight per compute unit, so the prefetch distance is a tuning knob.
   u32x4 kreg[PD][PIECES], vreg[PD][PIECES];
+  // Per-thread byte offsets of piece i inside a block that lies wholly in the
+  // cache or wholly in the suffix: (row, column) of the piece times the strides,
+  // computed once.  Such a block then costs one 64-bit add per load, on top of a
+  // wave-uniform base that the scalar unit computes; only the block that
+  // straddles the cache/suffix boundary, the ragged last block and the gather
+  // form take the general per-row path.
+  int64_t offc[PIECES], offs[PIECES];
+#pragma unroll
+  for (int i = 0; i < PIECES; ++i) {
+    const int pc = tid + NT * i;
+    offc[i] = (int64_t(pc / CPR) * a.cs[1] + 8 * (pc % CPR)) * 2;
+    offs[i] = (int64_t(pc / CPR) * a.ks[1] + 8 * (pc % CPR)) * 2;
+  }
   auto load_block = [&](int jb, u32x4 (&kr)[PIECES], u32x4 (&vr)[PIECES]) {
+    const int t0 = 32 * jb;
+    if (!GATHER && t0 + 32 <= P) {
+      const int64_t base = int64_t(t0) * a.cs[1] * 2;  // wave-uniform
+      const char *kb = reinterpret_cast<const char *>(kc) + base, *vb = reinterpret_cast<const char *>(vc) + base;
+#pragma unroll
+      for (int i = 0; i < PIECES; ++i) {
+        kr[i] = *reinterpret_cast<const u32x4 *>(kb + offc[i]);
+        vr[i] = *reinterpret_cast<const u32x4 *>(vb + offc[i]);
+      }
+      return;
+    }
+    if (t0 >= P && t0 + 32 <= T) {
+      const int64_t base = int64_t(t0 - P) * a.ks[1] * 2;
+      const char *kb = reinterpret_cast<const char *>(ks) + base, *vb = reinterpret_cast<const char *>(vs) + base;
+#pragma unroll
+      for (int i = 0; i < PIECES; ++i) {
+        kr[i] = *reinterpret_cast<const u32x4 *>(kb + offs[i]);
+        vr[i] = *reinterpret_cast<const u32x4 *>(vb + offs[i]);
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) {
       const int pc = tid + NT * i;
-      const int t = min(32 * jb + pc / CPR, T - 1);
+      const int t = min(t0 + pc / CPR, T - 1);
       const int64_t off = t < P ? int64_t(cache_row<GATHER>(a, b, t)) * a.cs[1] : int64_t(t - P) * a.ks[1];
       const uint16_t *kp = (t < P ? kc : ks) + off + 8 * (pc % CPR);
       const uint16_t *vp = (t < P ? vc : vs) + off + 8 * (pc % CPR);
