@@ -45,9 +45,30 @@ def test_argument_errors_are_reported_before_any_launch():
                          ctypes.c_size_t(0), None)
     assert rc == -1 and b"multiple" in L.lsp_last_error()
     c = lsp.CommitDesc(B=1, S=4, V=8, C=8, min_commit=-1)
-    rc = L.lsp_commit(ctypes.byref(c), None, None, None, None, None, None, None, None, None, None, None,
-                      None, None, None, None, None, ctypes.c_size_t(0), None)
+    commit_args = [None] * 17 + [ctypes.c_size_t(0), None]      # every pointer null: validation stops first
+    rc = L.lsp_commit(ctypes.byref(c), *commit_args)
     assert rc == -1
+    # the descriptor is checked field by field once the mandatory pointers are there
+    buf = (ctypes.c_int32 * 64)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    ptrs = [p, p, None, None, None, None, None, None, p, p, p, p, p, p, None, None, None, ctypes.c_size_t(0), None]
+    for bad, word in ((dict(min_commit=-1), b"min_commit"), (dict(max_commit=-2), b"max_commit"),
+                      (dict(adaptive=1, alpha=0.6, beta=0.5), b"alpha"), (dict(adaptive=1, alpha=0.0, beta=0.5), b"alpha"),
+                      (dict(snap_enabled=1), b"bitmap"), (dict(num_layers=2, Hkv=1, D=8, kv_dtype=1), b"layer")):
+        c = lsp.CommitDesc(**{**dict(B=1, S=4, V=8, C=8), **bad})
+        assert L.lsp_commit(ctypes.byref(c), *ptrs) == -1 and word in L.lsp_last_error(), bad
+    # Scattered-Margin entry points
+    assert L.lsp_select_scattered(None, 1, 4, None, None, None, None, None) == -1
+    assert L.lsp_select_scattered(p, 1, 100000, p, p, p, p, None) == -2 and b"exceeds" in L.lsp_last_error()
+    assert L.lsp_kv_gather_append(1, 1, 4, 1, 3, 8, 1, ctypes.c_int64(0), ctypes.c_int64(0), p, p, p, p, p, p, p, None, None) == -1
+    assert b"multiple of 16" in L.lsp_last_error()
+    d = lsp.AttnDesc(dtype=1, B=1, S=4, Hq=2, Hkv=2, D=128, C=8)
+    rc = L.lsp_attn_step_gather(ctypes.byref(d), p, p, p, p, p, None, p, p, p, None, ctypes.c_size_t(0), None)
+    assert rc == -1 and b"row index" in L.lsp_last_error()
+    d = lsp.AttnDesc(dtype=1, B=1, S=4, Hq=2, Hkv=2, D=96, C=8)
+    sixteen = ctypes.c_void_p((ctypes.addressof(buf) + 15) & ~15)
+    args = [sixteen] * 5 + [sixteen, sixteen, sixteen, None, ctypes.c_size_t(0), None]
+    assert L.lsp_attn_step(ctypes.byref(d), *args) == -2 and b"head_dim" in L.lsp_last_error()
 
 
 def test_missing_library_fails_loudly(monkeypatch):
