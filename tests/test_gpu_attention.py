@@ -155,3 +155,32 @@ def test_many_rows_ragged_lengths_sampled(lsp, oracle, D, Hq, Hkv, S):
     for b in range(w.B):
         assert torch.all(got[b, int(sl[b]):] == 123.0)
         assert not torch.isnan(got[b, : int(sl[b])]).any()
+
+
+def test_strided_views_many_rows_sampled(lsp, oracle):
+    """Q/K/V sliced out of one fused [B,S,Hq+2Hkv,D] buffer and a cache with padded
+    rows, at a size that takes the long-suffix launch shape."""
+    w = W.scaled(W.C2, B=2, S=520, P=300, C=384, Hq=32, Hkv=8, D=128, seed=17)
+    pl = torch.tensor([300, 123], dtype=torch.int32)
+    sl = torch.tensor([520, 407], dtype=torch.int32)
+    kv = W.make_layer_kv(w, 0, prefix_len=pl)
+    fused = torch.cat([kv["q"], kv["k_suf"], kv["v_suf"]], dim=2).cuda()
+    q, k, v = fused[:, :, :32], fused[:, :, 32:40], fused[:, :, 40:48]
+    pad_k = torch.zeros((2, 384, 12, 128), dtype=torch.bfloat16, device="cuda")
+    pad_v = torch.zeros_like(pad_k)
+    pad_k[:, :, 2:10] = kv["k_cache"].cuda()
+    pad_v[:, :, 2:10] = kv["v_cache"].cuda()
+    out = torch.full((2, 520, 32, 128), 123.0, dtype=torch.bfloat16, device="cuda")
+    lsp.attn_step(q, k, v, pad_k[:, :, 2:10], pad_v[:, :, 2:10], pl.cuda(), sl.cuda(), out=out)
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(6)
+    rows = []
+    for b in range(2):
+        n = int(sl[b])
+        rows += [[b, int(i), int(h)] for i, h in zip(torch.randint(0, n, (30,), generator=g), torch.randint(0, 32, (30,), generator=g))]
+        rows += [[b, 0, 0], [b, n - 1, 31]]
+    rows = torch.tensor(rows, dtype=torch.int32)
+    ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl, rows=rows)
+    got = out[rows[:, 0].long().cuda(), rows[:, 1].long().cuda(), rows[:, 2].long().cuda()].float().cpu()
+    assert (got - ref).abs().max().item() <= 2e-2
+    assert torch.all(out[1, 407:].float() == 123.0)
