@@ -305,13 +305,7 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
   const uint16_t *ks = static_cast<const uint16_t *>(a.k_suf) + b * a.ks[0] + g * a.ks[2];
   const uint16_t *vs = static_cast<const uint16_t *>(a.v_suf) + b * a.ks[0] + g * a.ks[2];
 
-  // Q fragments (B operand of S^T = K.Q^T): query lq of this wave, d = 16*kk + 8*hf + 0..7
-  const int qi = q0 + wm * 32 + lq;
-  const uint16_t *qp = static_cast<const uint16_t *>(a.q) + b * a.qs[0] + int64_t(min(qi, N - 1)) * a.qs[1] + h * a.qs[2];
   bf16x8 qf[KK];
-#pragma unroll
-  for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8 *>(qp + 16 * kk + 8 * hf);
-
   f32x16 oacc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
@@ -370,6 +364,28 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
   };
 
   if (wk < NB) load_kv(wk);
+  // (the first K/V block is already on its way)
+  // Q fragments (B operand of S^T = K.Q^T): query lq of this wave, d = 16*kk + 8*hf + 0..7.
+  // The WK waves of a query block need the same 32 rows: the workgroup fetches
+  // its WM*32 rows once, coalesced, into LDS (behind the wave regions), and every
+  // wave reads its fragments from there.  (Fetched per wave and per fragment,
+  // each load touched 32 rows for 32 bytes: four times the cache lines, times
+  // WK waves - 40 % of all L1 traffic of a short step.)
+  {
+    constexpr int QCOL = D / 8;  // 16-byte columns per row
+    unsigned char *qlds = smem + WM * WK * G::WAVE_LDS;
+    const uint16_t *qb = static_cast<const uint16_t *>(a.q) + b * a.qs[0] + h * a.qs[2];
+    for (int i = tid; i < WM * 32 * QCOL; i += 64 * WM * WK) {
+      const int r = i / QCOL, c = i % QCOL;
+      const u32x4 v = *reinterpret_cast<const u32x4 *>(qb + int64_t(min(q0 + r, N - 1)) * a.qs[1] + 8 * c);
+      *reinterpret_cast<u32x4 *>(qlds + r * G::KPITCH + 16 * c) = v;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk)
+    qf[kk] = *reinterpret_cast<const bf16x8 *>(smem + WM * WK * G::WAVE_LDS + (wm * 32 + lq) * G::KPITCH + (16 * kk + 8 * hf) * 2);
+
   for (int jb = wk; jb < NB; jb += WK) block(jb);
   merge_store<D, WM, WK>(a, oacc, mref, lsum, smem, b, h, q0, N);
 }
@@ -382,7 +398,7 @@ int32_t launch_g(AttnArgs a, hipStream_t st) {
     return LSP_ERR_UNSUPPORTED;
   }
   const dim3 grid(static_cast<unsigned>(nwg), 1, 1);
-  const size_t lds = size_t(WM * WK) * Geo<D>::WAVE_LDS;
+  const size_t lds = size_t(WM * WK) * Geo<D>::WAVE_LDS + size_t(WM) * 32 * Geo<D>::KPITCH;  // wave regions + Q rows
   auto kern = attn_bf16_kernel<D, WM, WK, GATHER>;
   static bool configured = false;  // per instantiation
   if (!configured) {
