@@ -15,8 +15,8 @@
 //     re-read once at the end - by the lanes that hold the wave's maximum only
 //     (every lane doing so would add 16 KB of scattered cache lines per wave);
 //   - the soft-max sum uses one exp2 per element against a lagging per-lane
-//     reference r (log2 domain) which is only moved when the lane maximum has
-//     run more than 32 octaves ahead of it, so the rescale branch is cold.  A
+//     reference r which is only moved when the lane maximum has run more than
+//     22 units (about 32 octaves) ahead of it, so the rescale branch is cold.  A
 //     group's top-2 pass runs before its sum pass, so the reference always
 //     covers the values being exponentiated.
 // Lane results are merged in two steps: the maximum first (DPP reduction), then
@@ -38,12 +38,12 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLagOctaves = 32.0f;
+constexpr float kLag = 22.0f;  // the reference may lag the maximum by this much (about 32 octaves)
 
 struct Top {
   float m1, m2;  // largest and second largest value seen (duplicates count)
-  float s;       // sum of exp2(x*log2e - r)
-  float r;       // reference exponent (log2 domain)
+  float s;       // sum of exp(x - r)
+  float r;       // reference value (a logit; the subtraction x - r is exact for the terms that matter)
   int idx;       // >= 0: element index of the first maximum; < 0: ~(first element of the lane's group holding it)
 };
 
@@ -76,9 +76,9 @@ __device__ __forceinline__ void absorb_top2(Top &t, const float (&x)[N]) {
 
 // Move the reference up when the maximum has run ahead of it (cold branch).
 __device__ __forceinline__ void settle_reference(Top &t) {
-  const float mc = t.m1 * kLog2e;
-  if (mc - t.r > kLagOctaves) {
-    t.s *= __builtin_amdgcn_exp2f(t.r - mc);
+  const float mc = t.m1;
+  if (mc - t.r > kLag) {
+    t.s *= __builtin_amdgcn_exp2f((t.r - mc) * kLog2e);
     t.r = mc;
   }
 }
@@ -86,9 +86,12 @@ __device__ __forceinline__ void settle_reference(Top &t) {
 // Soft-max sum over N values that are already covered by t.m1 / t.r.
 template <int N>
 __device__ __forceinline__ void absorb_sum(Top &t, const float (&x)[N]) {
-  const float nr = -t.r;
+  // x - r first: exact for values near the reference, which carry the sum.  (With
+  // fma(x, log2e, -r*log2e) the rounding of r*log2e shows up as a relative error
+  // of |r| * 4e-8 in every term: 2e-5 for logits around 500.)
+  const float r = t.r;
 #pragma unroll
-  for (int j = 0; j < N; ++j) t.s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[j], kLog2e, nr));
+  for (int j = 0; j < N; ++j) t.s += __builtin_amdgcn_exp2f((x[j] - r) * kLog2e);
 }
 
 template <int N>
@@ -173,7 +176,7 @@ __device__ __forceinline__ RowStat wave_combine(const Top &t, float wave_max) {
   const float second = wave_reduce(top ? t.m2 : t.m1, OpMax());
   o.m2 = ntop >= 2 ? o.m1 : second;  // the maximum held by two lanes is its own runner-up
   o.idx = __float_as_int(wave_reduce(__int_as_float(top ? t.idx : INT_MAX), OpMinI()));
-  const float w = __builtin_amdgcn_exp2f(t.r - o.m1 * kLog2e);  // 0 for an empty lane (r = -FLT_MAX)
+  const float w = __builtin_amdgcn_exp2f((t.r - o.m1) * kLog2e);  // 0 for an empty lane (r = -FLT_MAX)
   const float sum = wave_reduce(t.s * w, OpAdd());
   o.s = o.m1 == -INFINITY ? 0.f : sum;  // an all -inf segment has an empty sum
   return o;
@@ -309,7 +312,7 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
     if (lane < NW) {
       const RowStat w = lds[lane];
       t.m1 = w.m1; t.m2 = w.m2; t.s = w.s; t.idx = w.idx;
-      t.r = w.m1 == -INFINITY ? -FLT_MAX : w.m1 * kLog2e;
+      t.r = w.m1 == -INFINITY ? -FLT_MAX : w.m1;
     }
     r = wave_combine(t, wave_reduce(t.m1, OpMax()));
   }

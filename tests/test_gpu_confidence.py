@@ -154,3 +154,42 @@ def test_deterministic(lsp):
     torch.cuda.synchronize()
     for x, y in zip(a, b):
         assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_wide_dynamic_range_and_moving_maximum(lsp, oracle, dtype):
+    """Rows that force the lagging soft-max reference to move: a slow ramp (every
+    lane's maximum keeps rising), a late spike far above everything before it, an
+    early spike followed by a long flat tail, large negative offsets, and a row
+    whose sum is dominated by many near-maximal entries."""
+    V = 50021
+    z = torch.zeros((1, 6, V))
+    idx = torch.arange(V, dtype=torch.float32)
+    z[0, 0] = idx * (300.0 / V) - 150.0                    # ramp over 300 units
+    z[0, 1] = torch.randn(V, generator=torch.Generator().manual_seed(1))
+    z[0, 1, V - 5] = 500.0                                 # late spike
+    z[0, 2] = torch.randn(V, generator=torch.Generator().manual_seed(2))
+    z[0, 2, 2] = 250.0                                     # early spike
+    z[0, 3] = torch.randn(V, generator=torch.Generator().manual_seed(3)) - 3000.0
+    z[0, 4] = 40.0 - (idx % 7) * 0.125                     # thousands of entries at and near the maximum
+    z[0, 5] = -(idx * (200.0 / V))                         # falling ramp: the first entry is the maximum
+    z = z.to(dtype)
+    ids_r, p_r, m_r = _check(lsp, oracle, z)
+    assert ids_r[0, 1] == V - 5 and ids_r[0, 2] == 2 and ids_r[0, 5] == 0 and ids_r[0, 4] == 0
+    assert m_r[0, 4] == 0.0
+
+
+def test_unaligned_start_and_odd_lengths(lsp, oracle):
+    """Every alignment of the first element against a 16-byte boundary, vocab sizes
+    around the vector and group sizes, in both element types."""
+    g = torch.Generator().manual_seed(9)
+    for dtype, per16 in ((torch.bfloat16, 8), (torch.float32, 4)):
+        for off in range(per16):
+            for V in (per16 * 64 * 4 - 1, per16 * 64 * 4 + 1, 1031):
+                big = torch.randn((1, 3, V + off + 3), generator=g).to(dtype)
+                view = big[:, :, off:off + V]
+                ids, p, m = lsp.confidence(big.cuda()[:, :, off:off + V])
+                torch.cuda.synchronize()
+                ids_r, p_r, m_r = oracle.confidence(view.contiguous())
+                assert torch.equal(ids.cpu(), ids_r) and torch.equal(m.cpu(), m_r), (dtype, off, V)
+                assert (p.cpu() - p_r).abs().max().item() <= TOL[dtype]
