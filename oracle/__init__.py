@@ -84,6 +84,23 @@ def confidence(logits, suffix_len=None):
     return ids, prob, mar
 
 
+def lm_head_confidence(hidden, weight, suffix_len=None, return_logits=False):
+    """hidden [B,S,K], weight [V,K] -> (top1_id, top1_prob, margin) of the logits
+    hidden @ weight.T kept in double; with return_logits also z [B,S,V] float64."""
+    B, S, K = hidden.shape
+    V = weight.shape[0]
+    assert weight.shape[1] == K and weight.dtype == hidden.dtype
+    ids = torch.full((B, S), -1, dtype=torch.int32)
+    prob = torch.full((B, S), float("nan"), dtype=torch.float32)
+    mar = torch.full((B, S), float("nan"), dtype=torch.float32)
+    z = torch.full((B, S, V), float("nan"), dtype=torch.float64) if return_logits else None
+    sl = None if suffix_len is None else _i32(suffix_len)
+    rc = lib().oracle_lm_head_confidence(_dt(hidden), _p(hidden), _p(weight), B, S, K, V, _p(sl),
+                                         _p(ids), _p(prob), _p(mar), _p(z))
+    assert rc == 0, f"oracle_lm_head_confidence: non-finite logits (rc={rc})"
+    return (ids, prob, mar, z) if return_logits else (ids, prob, mar)
+
+
 def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
            prefix_len, suffix_len, tokens=None, k_suf=None, v_suf=None, k_cache=None, v_cache=None,
            C=None, adaptive=False, alpha=0.25, beta=0.5, max_commit=0):

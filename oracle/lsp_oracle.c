@@ -16,6 +16,9 @@
  *                        suffix's own K/V (Section 3.2, approximate KV caching).
  *   oracle_confidence  - top-1 id and logit margin of Eq. 1 (Algorithm 1
  *                        line 5), plus the top-1 soft-max probability.
+ *   oracle_lm_head_confidence - the output head (hidden state times the
+ *                        vocabulary matrix) feeding those same three results
+ *                        without ever storing the logits (Algorithm 1 lines 4-5).
  *   oracle_select_scattered, oracle_gather_append - the Scattered-Margin
  *                        baseline of Section 4.3.3 (same block size, scattered
  *                        positions) and the cache update it implies.
@@ -367,6 +370,53 @@ int oracle_gather_append(int kv_dtype, int B, int S, int Hkv, int D, int C, int 
         prefix_len[b] = P + k;
     }
     return 0;
+}
+
+/*
+ * The output head of the denoiser call followed by Eq. 1 (Algorithm 1 lines
+ * 4-5), with the logits kept in double and never rounded to a storage type:
+ *   z[r][v] = sum_k hidden[r][k] * weight[v][k]        (hidden [B*S, K], weight [V, K])
+ * then, per active row, the same three results as oracle_confidence: the lowest
+ * index attaining the maximum, the gap to the largest other entry, and
+ * 1 / sum_v exp(z_v - z1).  The margin is the double difference rounded once
+ * to fp32.  Optionally returns the full logits (z_out [B*S, V] doubles, may be
+ * NULL).  Rows i >= suffix_len[b] are left untouched.
+ */
+int oracle_lm_head_confidence(int dtype, const void *hidden, const void *weight,
+                              int B, int S, int K, int V, const int32_t *suffix_len,
+                              int32_t *top1_id, float *top1_prob, float *margin, double *z_out)
+{
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(| : bad)
+    for (int64_t r = 0; r < (int64_t)B * S; ++r) {
+        int b = (int)(r / S), i = (int)(r % S);
+        if (suffix_len && i >= suffix_len[b]) continue;
+        double *z = (double *)malloc(sizeof(double) * (size_t)V);
+        if (!z) { bad = 1; continue; }
+        for (int v = 0; v < V; ++v) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k)
+                acc += ld(hidden, dtype, r * K + k) * ld(weight, dtype, (int64_t)v * K + k);
+            z[v] = acc;
+            if (acc != acc) bad = 1;
+        }
+        int id = 0;
+        for (int v = 1; v < V; ++v)
+            if (z[v] > z[id]) id = v;
+        double z2 = -INFINITY;
+        for (int v = 0; v < V; ++v)
+            if (v != id && z[v] > z2) z2 = z[v];
+        if (!(z[id] > -INFINITY && z[id] < INFINITY)) bad = 1;
+        double den = 0.0;
+        for (int v = 0; v < V; ++v)
+            den += exp(z[v] - z[id]);
+        top1_id[r] = id;
+        margin[r] = (float)(z[id] - z2);
+        top1_prob[r] = (float)(1.0 / den);
+        if (z_out) memcpy(z_out + r * V, z, sizeof(double) * (size_t)V);
+        free(z);
+    }
+    return bad ? -2 : 0;
 }
 
 /* Threads the OpenMP loops above will use (reported next to oracle timings). */

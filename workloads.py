@@ -216,6 +216,26 @@ def make_logits(w: Workload, device="cpu", step: int = 0, prefix_len=None, stabl
     return z.to(w.torch_dtype), info
 
 
+def make_lm_head(w: Workload, K: int, device="cpu", step: int = 0):
+    """Operands of the output head for the workload's rows: weight [V,K] ~
+    N(0, 1/K) and hidden [B,S,K] ~ N(0,1), both rounded to the storage type, so
+    that the logits hidden @ weight.T are ~ N(0,1) like make_logits' background.
+    Row i additionally gets boost * exp(-i/decay) (plant "decay") or boost (any
+    other plant) times weight[t_i] / |weight[t_i]|^2 added to its hidden state,
+    which lifts the logit of the planted id t_i by that amount.
+    Returns (hidden, weight, info) with info = dict(planted_id [B,S])."""
+    g = _gen(w.seed + 57 + 7919 * step, device)
+    delim_ids, _ = make_delimiters(w)
+    weight = (torch.randn((w.V, K), generator=g, device=device, dtype=torch.float32) / math.sqrt(K)).to(w.torch_dtype)
+    hidden = torch.randn((w.B, w.S, K), generator=g, device=device, dtype=torch.float32)
+    tid = _planted_ids(w, delim_ids, (w.B, w.S), g, device)
+    pos = torch.arange(w.S, device=device, dtype=torch.float32)
+    amp = w.boost * torch.exp(-pos / w.decay) if w.plant == "decay" else torch.full_like(pos, w.boost)
+    wt = weight[tid.reshape(-1)].float().view(w.B, w.S, K)
+    hidden += amp.view(1, w.S, 1) * wt / (wt * wt).sum(-1, keepdim=True)
+    return hidden.to(w.torch_dtype), weight, {"planted_id": tid}
+
+
 def make_process_logits(w: Workload, device, step: int, prefix_len):
     """Config-5 style synthetic denoising process.
 
