@@ -247,6 +247,41 @@ int32_t lsp_attn_step_gather(const lsp_attn_desc *desc, const void *q, const voi
                              size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------- *
+ * Output head fused with the per-position confidence (Algorithm 1 lines 4-5:
+ * the last projection of the denoiser call p_theta, then Eq. 1).
+ *
+ * For every sequence b and active row i < N_b the logits
+ *     z[v] = sum_k hidden[b,i,k] * weight[v,k]       (bf16 operands, fp32 sums)
+ * are produced tile by tile on the matrix cores and reduced at once to
+ * top1_id / margin / top1_prob, defined exactly as for lsp_confidence on z; z
+ * itself is never written to memory and is NOT rounded to bf16, so margins and
+ * probabilities differ from "GEMM, store bf16 logits, lsp_confidence" by that
+ * rounding.  Summation order is the kernel's: results match an exact
+ * evaluation to fp32 accumulation error (about 1e-6 * sum_k |h_k w_k|), and the
+ * id is the exact arg-max wherever the exact margin exceeds that error.
+ * Rows i >= N_b are not written.
+ * ------------------------------------------------------------------------- */
+size_t lsp_lm_head_confidence_workspace_bytes(int32_t B, int32_t S, int32_t V);
+
+/*
+ * dtype: LSP_BF16 only (LSP_ERR_UNSUPPORTED otherwise).  hidden: device, row
+ * (b,i) = K elements at b*hidden_batch_stride + i*hidden_row_stride (0 selects
+ * dense S*K / K).  weight: device, vocabulary entry v = K elements at
+ * v*weight_row_stride (0 = K) - the usual [V, K] layout of an output
+ * embedding.  K a multiple of 8; pointers 16-byte aligned and strides multiples
+ * of 8 elements.  suffix_len: device int32[B] or NULL (= all S rows active).
+ * top1_id (int32), top1_prob (fp32), margin (fp32): device, [B,S] dense.
+ * workspace: device, 16-byte aligned, at least
+ * lsp_lm_head_confidence_workspace_bytes(B,S,V) bytes (per row and 256-entry
+ * vocabulary tile one 16-byte partial result).
+ */
+int32_t lsp_lm_head_confidence(int32_t dtype, const void *hidden, const void *weight, int32_t B,
+                               int32_t S, int32_t K, int32_t V, int64_t hidden_row_stride,
+                               int64_t hidden_batch_stride, int64_t weight_row_stride,
+                               const int32_t *suffix_len, int32_t *top1_id, float *top1_prob,
+                               float *margin, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- *
  * Flip bookkeeping for a decode loop (Section 4.3.4: share of active-suffix
  * positions whose top-1 prediction changes between consecutive steps).
  *

@@ -46,7 +46,7 @@ class CommitDesc(ctypes.Structure):
 EXPORTS = ["lsp_version", "lsp_last_error", "lsp_attn_workspace_bytes", "lsp_attn_step",
            "lsp_confidence_workspace_bytes", "lsp_confidence", "lsp_commit_workspace_bytes",
            "lsp_commit", "lsp_flip_update", "lsp_select_scattered", "lsp_kv_gather_append",
-           "lsp_attn_step_gather"]
+           "lsp_attn_step_gather", "lsp_lm_head_confidence_workspace_bytes", "lsp_lm_head_confidence"]
 
 
 def lib() -> ctypes.CDLL:
@@ -59,10 +59,11 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(LIB_PATH)
         L.lsp_version.restype = ctypes.c_char_p
         L.lsp_last_error.restype = ctypes.c_char_p
-        for n in ("lsp_attn_workspace_bytes", "lsp_confidence_workspace_bytes", "lsp_commit_workspace_bytes"):
+        for n in ("lsp_attn_workspace_bytes", "lsp_confidence_workspace_bytes", "lsp_commit_workspace_bytes",
+                  "lsp_lm_head_confidence_workspace_bytes"):
             getattr(L, n).restype = ctypes.c_size_t
         for n in ("lsp_attn_step", "lsp_confidence", "lsp_commit", "lsp_flip_update", "lsp_select_scattered",
-                  "lsp_kv_gather_append", "lsp_attn_step_gather"):
+                  "lsp_kv_gather_append", "lsp_attn_step_gather", "lsp_lm_head_confidence"):
             getattr(L, n).restype = ctypes.c_int32
         _lib = L
     return _lib
@@ -167,6 +168,31 @@ def confidence(logits, suffix_len=None, out=None, workspace=None):
                               _ptr(suffix_len), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]),
                               _ptr(workspace), ctypes.c_size_t(wb), _stream())
     _check(rc, "lsp_confidence")
+    return out
+
+
+def lm_head_confidence(hidden, weight, suffix_len=None, out=None, workspace=None):
+    """lsp_lm_head_confidence: hidden [B,S,K], weight [V,K] (bf16) ->
+    (top1_id int32, top1_prob f32, margin f32), [B,S], of the logits hidden @ weight.T,
+    which are never stored."""
+    _dev(hidden, weight, suffix_len)
+    B, S, K = hidden.shape
+    V = weight.shape[0]
+    assert weight.shape[1] == K and hidden.stride(2) == 1 and weight.stride(1) == 1
+    if out is None:
+        out = (torch.empty((B, S), dtype=torch.int32, device=hidden.device),
+               torch.empty((B, S), dtype=torch.float32, device=hidden.device),
+               torch.empty((B, S), dtype=torch.float32, device=hidden.device))
+    need = lib().lsp_lm_head_confidence_workspace_bytes(B, S, V)
+    if workspace is None or workspace.numel() * workspace.element_size() < need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=hidden.device)
+    wb = workspace.numel() * workspace.element_size()
+    rc = lib().lsp_lm_head_confidence(_dtype(hidden), _ptr(hidden), _ptr(weight), B, S, K, V,
+                                      ctypes.c_int64(hidden.stride(1)), ctypes.c_int64(hidden.stride(0)),
+                                      ctypes.c_int64(weight.stride(0)),
+                                      _ptr(suffix_len), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]),
+                                      _ptr(workspace), ctypes.c_size_t(wb), _stream())
+    _check(rc, "lsp_lm_head_confidence")
     return out
 
 

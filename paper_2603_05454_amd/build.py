@@ -8,7 +8,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblsp.so")
 SOURCES = ["lsp_common.hip", "lsp_confidence.hip", "lsp_commit.hip", "lsp_attn.hip",
-           "lsp_attn_f32.hip", "lsp_attn_bf16.hip", "lsp_scattered.hip"]
+           "lsp_attn_f32.hip", "lsp_attn_bf16.hip", "lsp_scattered.hip", "lsp_lm_head.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-result"]
