@@ -47,8 +47,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "scatter"],
-                    help="c1..c4: one step; c5: the decode loop; scatter: prefix-first against Scattered-Margin commits")
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "scatter", "lmhead"],
+                    help="c1..c4: one step; c5: the decode loop; scatter: prefix-first against Scattered-Margin commits; "
+                         "lmhead: output head fused with the confidence reduction against library GEMM + lsp_confidence")
     ap.add_argument("--sizing", default="tau", choices=["tau", "adaptive", "full"],
                     help="c5: fixed threshold (default), adaptive threshold (Eq. 2, [0.25, 0.5]) or the Full baseline (1 position per step)")
     ap.add_argument("--loop-steps", type=int, default=0, help="c5: stop the decode loop after this many steps (0 = run to the end)")
@@ -411,6 +412,57 @@ def run_scatter_comparison(layers=32):
             "attention_ratio_indexed_over_contiguous": round(t_attn_g / t_attn, 3)}
 
 
+def run_lm_head_comparison(K=4096):
+    """Output head fused with the confidence reduction (logits never stored) against the
+    unfused path: the library's bf16 GEMM writing [rows, V] bf16 logits, then lsp_confidence.
+    Config-2 and config-4 rows and vocabulary, hidden size 4096 (LLaDA-8B), random weights."""
+    import torch
+    import paper_2603_05454_amd as lsp
+    import workloads as W
+
+    dev = torch.device("cuda:0")
+    res = {}
+    for w in (W.C2, W.C4):
+        hidden, weight, _ = W.make_lm_head(w, K, device=dev)
+        rows = w.B * w.S
+        out = lsp.lm_head_confidence(hidden, weight)
+        ws = torch.empty(lsp.lib().lsp_lm_head_confidence_workspace_bytes(w.B, w.S, w.V), dtype=torch.uint8, device=dev)
+        z = torch.empty((w.B, w.S, w.V), dtype=torch.bfloat16, device=dev)
+        cws = torch.empty(max(16, lsp.confidence_workspace_bytes(w.B, w.S, w.V)), dtype=torch.uint8, device=dev)
+        out2 = tuple(torch.empty_like(t) for t in out)
+
+        def timed(fn, reps):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) * 1e-3 / reps
+
+        reps = 20 if rows > 1024 else 100
+        t_fused = timed(lambda: lsp.lm_head_confidence(hidden, weight, out=out, workspace=ws), reps)
+        t_gemm = timed(lambda: torch.matmul(hidden, weight.t(), out=z), reps)
+        t_conf = timed(lambda: lsp.confidence(z, out=out2, workspace=cws), reps)
+        flop = 2.0 * rows * w.V * K
+        agree = float((out[0] == out2[0]).float().mean().item())   # bf16-rounded logits can flip near-ties
+        res[w.name] = {"rows": rows, "V": w.V, "K": K, "flop": flop,
+                       "fused_us": round(t_fused * 1e6, 1), "fused_TFLOPs": round(flop / t_fused / 1e12, 1),
+                       "fused_frac_of_2.5PFLOPs": round(flop / t_fused / 2.5e15, 3),
+                       "library_gemm_us": round(t_gemm * 1e6, 1), "library_gemm_TFLOPs": round(flop / t_gemm / 1e12, 1),
+                       "lsp_confidence_us": round(t_conf * 1e6, 1),
+                       "unfused_total_us": round((t_gemm + t_conf) * 1e6, 1),
+                       "fused_over_unfused_time": round(t_fused / (t_gemm + t_conf), 3),
+                       "logits_bytes_not_written_or_read": 2 * rows * w.V * 2,
+                       "top1_id_agreement_with_unfused": round(agree, 5)}
+        del hidden, weight, z
+        torch.cuda.empty_cache()
+    return res
+
+
 def calibrate_copy():
     """A plain device-to-device copy of known size (1 GiB read + 1 GiB written per
     launch, 5 launches): what rocprofv3's FETCH_SIZE / WRITE_SIZE counters read
@@ -442,6 +494,10 @@ def main():
     if args.workload == "scatter":
         print(json.dumps({"comparison": "prefix-first vs Scattered-Margin (Section 4.3.3)", "n_gpus": 1, "dtype": "bf16",
                           "data": "synthetic", **run_scatter_comparison(args.layers or 32)}))
+        return
+    if args.workload == "lmhead":
+        print(json.dumps({"comparison": "output head fused with Eq. 1 vs library GEMM + lsp_confidence (Algorithm 1 lines 4-5)",
+                          "n_gpus": 1, "dtype": "bf16", "data": "synthetic", **run_lm_head_comparison()}))
         return
     if args.workload == "c5":
         value, ms, config = run_loop_workload(args.loop_steps, args.sizing)

@@ -19,6 +19,9 @@
 // RB row tiles: each weight slice is then read by RB and each hidden slice by
 // VB workgroups out of the same L2.
 #include <float.h>
+#ifdef LSP_TUNE
+#include <stdlib.h>
+#endif
 
 #include "lsp_common.h"
 
@@ -34,14 +37,8 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr int TV = 256;          // vocabulary entries per tile
 constexpr int TR = 256;          // rows per tile
 constexpr int BK = 64;           // K step
-constexpr int PITCH = BK * 2 + 16;  // bytes per staged row: 144 = 9 * 16, so 16 consecutive rows hit 16 distinct 16-byte slots of a 256-byte bank line
-constexpr int TILE_BYTES = 256 * PITCH;
-constexpr int STAGE = 2 * TILE_BYTES;  // weight tile, then hidden tile
-constexpr int NT = 512;          // 8 waves: 2 along the vocabulary x 4 along the rows
-constexpr int WV = 2, WR = 4;
-constexpr int MV = TV / WV / 32;  // 32x32 blocks per wave along the vocabulary (4)
-constexpr int MR = TR / WR / 32;  // ... along the rows (2)
-constexpr int PIECES = 256 * (BK / 8) / NT;  // 16-byte pieces per thread per operand tile and K step (4)
+constexpr int TILE_BYTES = 256 * BK * 2;  // one operand tile of a K step in LDS: 256 rows of 128 bytes
+constexpr int STAGE = 2 * TILE_BYTES;     // weight tile, then hidden tile
 
 struct Partial {
   float m1, m2, s;
@@ -102,8 +99,20 @@ __device__ __forceinline__ void tile_of(const LmArgs &a, int &vt, int &rt) {
   if (vt >= a.VT || rt >= a.RT) vt = -1;
 }
 
-__global__ __launch_bounds__(NT, 2) void lm_head_kernel(LmArgs a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+// One wave-wide load from global memory straight into LDS: lane l fetches 16
+// bytes at its own address g and they land at lds_base + 16 l (lds_base is
+// wave-uniform; the counter to wait on is vmcnt).
+__device__ __forceinline__ void load_to_lds(const char *g, unsigned char *lds_base) {
+  __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void *)lds_base, 16, 0, 0);
+}
+
+// WV x WR waves: WV along the vocabulary, WR along the rows.
+template <int WV, int WR>
+__global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) void lm_head_kernel(LmArgs a) {
+  constexpr int NT = 64 * WV * WR;
+  constexpr int MV = TV / WV / 32;  // 32x32 blocks per wave along the vocabulary
+  constexpr int MR = TR / WR / 32;  // ... along the rows
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   __shared__ int s_any;
   int vt, rt;
   tile_of(a, vt, rt);
@@ -119,46 +128,56 @@ __global__ __launch_bounds__(NT, 2) void lm_head_kernel(LmArgs a) {
     if (tid == 0) s_any = 0;
     __syncthreads();
     bool act = false;
-    if (tid < TR) {
-      const int r = r0 + tid;
-      if (r < rows) act = (r % a.S) < a.suffix_len[r / a.S];
+    for (int t = tid; t < TR; t += NT) {
+      const int r = r0 + t;
+      if (r < rows) act |= (r % a.S) < a.suffix_len[r / a.S];
     }
     if (act) s_any = 1;
     __syncthreads();
     if (!s_any) return;
   }
 
-  // loader: piece i of this thread is (tile row, 16-byte column) = ((tid + NT*i) / 8, (tid + NT*i) % 8)
-  const char *wp[PIECES], *hp[PIECES];
-  int lds_off[PIECES];
-  const int pcol = tid & 7;
+  // Loader.  Operand tiles go from global memory straight into LDS
+  // (global_load_lds_dwordx4: lane l of a wave-wide load deposits its 16 bytes at
+  // LDS base + 16 l, so one load fills 1 KB = 8 tile rows of 128 bytes).  Rows
+  // are stored unpadded; to keep the fragment reads (16 consecutive rows, one
+  // 16-byte chunk each) on distinct banks, chunk c of row r is kept at chunk
+  // position c ^ ((r >> 1) & 7), which the loading lane applies to its GLOBAL
+  // address.  Wave w issues loads w, w + NW, ... of the tile's 32.
+  constexpr int NW = NT / 64;
+  constexpr int LPW = 32 / NW;  // wave-wide loads per wave, per operand tile and K step
+  const char *wp[LPW], *hp[LPW];
+  int chunk[LPW];
 #pragma unroll
-  for (int i = 0; i < PIECES; ++i) {
-    const int prow = (tid + NT * i) >> 3;
-    const int v = min(v0 + prow, a.V - 1);     // rows beyond V or the row count repeat the last valid one
-    const int r = min(r0 + prow, rows - 1);    // (their results are masked or never written)
-    wp[i] = reinterpret_cast<const char *>(a.weight + int64_t(v) * a.wrs) + 16 * pcol;
-    hp[i] = reinterpret_cast<const char *>(a.hidden + int64_t(r / a.S) * a.hbs + int64_t(r % a.S) * a.hrs) + 16 * pcol;
-    lds_off[i] = prow * PITCH + 16 * pcol;
+  for (int i = 0; i < LPW; ++i) {
+    const int row = 8 * (wave + NW * i) + (lane >> 3);
+    chunk[i] = (lane & 7) ^ ((row >> 1) & 7);
+    const int v = min(v0 + row, a.V - 1);     // rows beyond V or the row count repeat the last valid one
+    const int r = min(r0 + row, rows - 1);    // (their results are masked or never written)
+    wp[i] = reinterpret_cast<const char *>(a.weight + int64_t(v) * a.wrs) + 16 * chunk[i];
+    hp[i] = reinterpret_cast<const char *>(a.hidden + int64_t(r / a.S) * a.hbs + int64_t(r % a.S) * a.hrs) + 16 * chunk[i];
   }
   const int KS = (a.K + BK - 1) / BK;
-  u32x4 wreg[PIECES], hreg[PIECES];
-  auto load_stage = [&](int ks) {
-    const int kbyte = ks * BK * 2;
-    const bool in = (ks * BK + 8 * pcol) < a.K;  // K tail: pieces beyond K are zeros
-#pragma unroll
-    for (int i = 0; i < PIECES; ++i) {
-      wreg[i] = in ? *reinterpret_cast<const u32x4 *>(wp[i] + kbyte) : u32x4{0, 0, 0, 0};
-      hreg[i] = in ? *reinterpret_cast<const u32x4 *>(hp[i] + kbyte) : u32x4{0, 0, 0, 0};
-    }
+  const int tail_chunks = (a.K % BK) / 8;  // valid 16-byte chunks of a ragged last step (0 = none ragged)
+  auto issue = [&](int ks, int i) {
+    unsigned char *st = smem + (ks & 1) * STAGE + 1024 * (wave + NW * i);
+    int back = 0;  // a lane whose chunk lies beyond K fetches the row's chunk 0 of this step instead (zeroed below)
+    if (tail_chunks != 0 && ks == KS - 1 && chunk[i] >= tail_chunks) back = 16 * chunk[i];
+    const int kbyte = ks * BK * 2 - back;
+    load_to_lds(wp[i] + kbyte, st);
+    load_to_lds(hp[i] + kbyte, st + TILE_BYTES);
   };
-  auto store_stage = [&](int ks) {
-    unsigned char *st = smem + (ks & 1) * STAGE;
+  // after the loads of a ragged last step have landed: the lanes that fetched a
+  // stand-in overwrite their own LDS slots with zeros
+  auto zero_tail = [&](int ks) {
+    if (tail_chunks == 0 || ks != KS - 1) return;
 #pragma unroll
-    for (int i = 0; i < PIECES; ++i) {
-      *reinterpret_cast<u32x4 *>(st + lds_off[i]) = wreg[i];
-      *reinterpret_cast<u32x4 *>(st + TILE_BYTES + lds_off[i]) = hreg[i];
-    }
+    for (int i = 0; i < LPW; ++i)
+      if (chunk[i] >= tail_chunks) {
+        unsigned char *st = smem + (ks & 1) * STAGE + 1024 * (wave + NW * i) + 16 * lane;
+        *reinterpret_cast<u32x4 *>(st) = u32x4{0, 0, 0, 0};
+        *reinterpret_cast<u32x4 *>(st + TILE_BYTES) = u32x4{0, 0, 0, 0};
+      }
   };
 
   f32x16 acc[MV][MR];
@@ -169,39 +188,47 @@ __global__ __launch_bounds__(NT, 2) void lm_head_kernel(LmArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  load_stage(0);
-  store_stage(0);
-  if (KS > 1) load_stage(1);
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) issue(0, i);
+  __builtin_amdgcn_s_waitcnt(0);  // vmcnt = 0: the loads have written LDS
+  zero_tail(0);
   __syncthreads();
-  const int a_off = (wv * (TV / WV) + lq) * PITCH + 16 * hf;
-  const int b_off = TILE_BYTES + (wr * (TR / WR) + lq) * PITCH + 16 * hf;
+  // fragment of 32x32 block i at k-step kk: row (block base + lq), chunk 2 kk + hf, swizzled
+  const int y16 = 16 * (hf ^ ((lq >> 1) & 7));
+  const int a_row = (wv * (TV / WV) + lq) * 128;
+  const int b_row = TILE_BYTES + (wr * (TR / WR) + lq) * 128;
   for (int ks = 0; ks < KS; ++ks) {
-    // stage ks+1 goes into the buffer every wave finished reading before the last barrier
-    if (ks + 1 < KS) store_stage(ks + 1);
-    if (ks + 2 < KS) load_stage(ks + 2);
+    // step ks+1 is fetched into the buffer every wave finished reading before the last barrier
+    if (ks + 1 < KS) {
+#pragma unroll
+      for (int i = 0; i < LPW; ++i) issue(ks + 1, i);
+    }
     const unsigned char *st = smem + (ks & 1) * STAGE;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
+      const int off = (32 * kk) ^ y16;
       bf16x8 af[MV], bf[MR];
 #pragma unroll
-      for (int i = 0; i < MV; ++i) af[i] = *reinterpret_cast<const bf16x8 *>(st + a_off + i * 32 * PITCH + kk * 32);
+      for (int i = 0; i < MV; ++i) af[i] = *reinterpret_cast<const bf16x8 *>(st + a_row + i * 32 * 128 + off);
 #pragma unroll
-      for (int j = 0; j < MR; ++j) bf[j] = *reinterpret_cast<const bf16x8 *>(st + b_off + j * 32 * PITCH + kk * 32);
+      for (int j = 0; j < MR; ++j) bf[j] = *reinterpret_cast<const bf16x8 *>(st + b_row + j * 32 * 128 + off);
 #pragma unroll
       for (int i = 0; i < MV; ++i)
 #pragma unroll
         for (int j = 0; j < MR; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
     }
+    __builtin_amdgcn_s_waitcnt(0);  // this wave's share of step ks+1 is in LDS
+    zero_tail(ks + 1);
     __syncthreads();
   }
 
   // ---- Eq. 1 on the accumulators ------------------------------------------------
-  // acc[i][j][r] = z[v][row] with v = v0 + wv*128 + 32 i + 8 (r/4) + 4 hf + r%4 (increasing
-  // in (i, r)) and row = r0 + wr*64 + 32 j + lq.
+  // acc[i][j][r] = z[v][row] with v = v0 + wv*(TV/WV) + 32 i + 8 (r/4) + 4 hf + r%4
+  // (increasing in (i, r)) and row = r0 + wr*(TR/WR) + 32 j + lq.
   const int vbase = v0 + wv * (TV / WV) + 4 * hf;
   const bool ragged = v0 + TV > a.V;
-  Partial *lds_part = reinterpret_cast<Partial *>(smem);  // [WR][MR][WV][32] after the last barrier
+  Partial *lds_part = reinterpret_cast<Partial *>(smem);  // [TR][WV] after the last barrier
 #pragma unroll
   for (int j = 0; j < MR; ++j) {
     float m1 = -INFINITY, m2 = -INFINITY;
@@ -229,16 +256,15 @@ __global__ __launch_bounds__(NT, 2) void lm_head_kernel(LmArgs a) {
     Partial o;
     o.m1 = __shfl_xor(p.m1, 32); o.m2 = __shfl_xor(p.m2, 32); o.s = __shfl_xor(p.s, 32); o.idx = __shfl_xor(p.idx, 32);
     p = fold(p, o);
-    if (hf == 0) lds_part[((wr * MR + j) * WV + wv) * 32 + lq] = p;
+    if (hf == 0) lds_part[(wr * (TR / WR) + 32 * j + lq) * WV + wv] = p;
   }
   __syncthreads();
   // one thread per row of the tile folds the WV waves' results and writes the partial
-  if (tid < TR) {
-    const int w = tid >> 6, j = (tid >> 5) & 1, q = tid & 31;  // tid = w*64 + j*32 + q = row within the tile
-    Partial p = lds_part[((w * MR + j) * WV + 0) * 32 + q];
+  for (int t = tid; t < TR; t += NT) {
+    Partial p = lds_part[t * WV];
 #pragma unroll
-    for (int u = 1; u < WV; ++u) p = fold(p, lds_part[((w * MR + j) * WV + u) * 32 + q]);
-    const int r = r0 + tid;
+    for (int u = 1; u < WV; ++u) p = fold(p, lds_part[t * WV + u]);
+    const int r = r0 + t;
     if (r < rows) a.partials[int64_t(r) * a.VT + vt] = p;
   }
 }
@@ -267,6 +293,30 @@ __global__ __launch_bounds__(256) void lm_head_finish_kernel(const Partial *__re
     margin[r] = p.m1 - p.m2;
     top1_prob[r] = 1.0f / p.s;
   }
+}
+
+template <int WV, int WR>
+int32_t launch_lm_head_t(const LmArgs &a, int64_t nwg, hipStream_t st) {
+  const size_t lds = 2 * size_t(STAGE);  // two K steps in LDS
+  auto kern = lm_head_kernel<WV, WR>;
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+    if (e != hipSuccess) return hip_fail(e, "lsp_lm_head_confidence: hipFuncSetAttribute");
+    configured = true;
+  }
+  kern<<<dim3(static_cast<unsigned>(nwg)), 64 * WV * WR, lds, st>>>(a);
+  LSP_CHECK_LAUNCH("lsp_lm_head_confidence: launch");
+  return LSP_OK;
+}
+
+int32_t launch_lm_head(const LmArgs &a, int64_t nwg, hipStream_t st) {
+#ifdef LSP_TUNE
+  const char *v = getenv("LSP_LM_VARIANT");
+  if (v && atoi(v) == 1) return launch_lm_head_t<2, 2>(a, nwg, st);
+#endif
+  return launch_lm_head_t<2, 4>(a, nwg, st);
 }
 
 }  // namespace
@@ -327,16 +377,8 @@ extern "C" int32_t lsp_lm_head_confidence(int32_t dtype, const void *hidden, con
     return LSP_ERR_UNSUPPORTED;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const size_t lds = 2 * size_t(STAGE);
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lm_head_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
-    if (e != hipSuccess) return hip_fail(e, "lsp_lm_head_confidence: hipFuncSetAttribute");
-    configured = true;
-  }
-  lm_head_kernel<<<dim3(static_cast<unsigned>(nwg)), NT, lds, st>>>(a);
-  LSP_CHECK_LAUNCH("lsp_lm_head_confidence: launch");
+  const int32_t rc = launch_lm_head(a, nwg, st);
+  if (rc != LSP_OK) return rc;
   lm_head_finish_kernel<<<dim3(static_cast<unsigned>((rows + 3) / 4)), 256, 0, st>>>(
       a.partials, int(rows), S, a.VT, suffix_len, top1_id, top1_prob, margin);
   LSP_CHECK_LAUNCH("lsp_lm_head_confidence: finish launch");
