@@ -14,6 +14,13 @@
 // (row, vocabulary tile) leaves one 16-byte partial; a second, tiny kernel
 // folds a row's partials.
 //
+// Main loop.  Both operand tiles of a K step go from global memory straight
+// into LDS (no registers, no LDS store instructions), one step ahead of the
+// products, into the buffer freed at the last barrier.  Fragments of k-step
+// kk+1 are read while the matrix instructions of kk run, and the issue order
+// of a whole step is pinned: one LDS read or one global load after each matrix
+// instruction, global loads first.
+//
 // Tiles go to the 8 XCDs round-robin by workgroup id; ids are laid out so that
 // the 32 workgroups an XCD runs at a time form a block of VB vocabulary tiles x
 // RB row tiles: each weight slice is then read by RB and each hidden slice by
@@ -106,8 +113,16 @@ __device__ __forceinline__ void load_to_lds(const char *g, unsigned char *lds_ba
   __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void *)lds_base, 16, 0, 0);
 }
 
-// WV x WR waves: WV along the vocabulary, WR along the rows.
-template <int WV, int WR>
+// 4 bytes per lane into LDS (lane l lands at lds_base + 4 l): used only to pull
+// 64 cache lines, one per lane, into L2 ahead of time.
+__device__ __forceinline__ void touch_to_lds(const char *g, unsigned char *lds_base) {
+  __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void *)lds_base, 4, 0, 0);
+}
+
+// WV x WR waves: WV along the vocabulary, WR along the rows.  PF > 0: every
+// step also touches the operand lines of the step PF ahead, so that the real
+// loads, one step ahead, find them in L2.
+template <int WV, int WR, int PF>
 __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) void lm_head_kernel(LmArgs a) {
   constexpr int NT = 64 * WV * WR;
   constexpr int MV = TV / WV / 32;  // 32x32 blocks per wave along the vocabulary
@@ -145,6 +160,7 @@ __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) vo
   // position c ^ ((r >> 1) & 7), which the loading lane applies to its GLOBAL
   // address.  Wave w issues loads w, w + NW, ... of the tile's 32.
   constexpr int NW = NT / 64;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);  // wave-uniform, for the scalar LDS base
   constexpr int LPW = 32 / NW;  // wave-wide loads per wave, per operand tile and K step
   const char *wp[LPW], *hp[LPW];
   int chunk[LPW];
@@ -157,10 +173,26 @@ __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) vo
     wp[i] = reinterpret_cast<const char *>(a.weight + int64_t(v) * a.wrs) + 16 * chunk[i];
     hp[i] = reinterpret_cast<const char *>(a.hidden + int64_t(r / a.S) * a.hbs + int64_t(r % a.S) * a.hrs) + 16 * chunk[i];
   }
+  // L2 warm-up: a step's operand tiles are 2 x 256 rows x one 128-byte line; eight
+  // wave-wide 4-byte loads with the lanes one row apart touch them all.
+  constexpr int PFI = PF > 0 ? 8 / NW : 0;
+  const char *pfp[PFI > 0 ? PFI : 1];
+#pragma unroll
+  for (int j = 0; j < PFI; ++j) {
+    const int idx = wave + NW * j, row = 64 * (idx & 3) + lane;
+    const int v = min(v0 + row, a.V - 1), r = min(r0 + row, rows - 1);
+    pfp[j] = idx < 4 ? reinterpret_cast<const char *>(a.weight + int64_t(v) * a.wrs)
+                     : reinterpret_cast<const char *>(a.hidden + int64_t(r / a.S) * a.hbs + int64_t(r % a.S) * a.hrs);
+  }
   const int KS = (a.K + BK - 1) / BK;
+  auto touch = [&](int ks) {  // lines of step ks (clamped: the last steps touch the last step again)
+    const int kbyte = min(ks, KS - 1) * BK * 2;
+#pragma unroll
+    for (int j = 0; j < PFI; ++j) touch_to_lds(pfp[j] + kbyte, smem + 2 * STAGE + 256 * (wave_s + NW * j));
+  };
   const int tail_chunks = (a.K % BK) / 8;  // valid 16-byte chunks of a ragged last step (0 = none ragged)
-  auto issue = [&](int ks, int i) {
-    unsigned char *st = smem + (ks & 1) * STAGE + 1024 * (wave + NW * i);
+  auto issue = [&](int ks, int buf, int i) {
+    unsigned char *st = smem + buf * STAGE + 1024 * (wave_s + NW * i);
     int back = 0;  // a lane whose chunk lies beyond K fetches the row's chunk 0 of this step instead (zeroed below)
     if (tail_chunks != 0 && ks == KS - 1 && chunk[i] >= tail_chunks) back = 16 * chunk[i];
     const int kbyte = ks * BK * 2 - back;
@@ -189,7 +221,9 @@ __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) vo
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
 #pragma unroll
-  for (int i = 0; i < LPW; ++i) issue(0, i);
+  for (int i = 0; i < LPW; ++i) issue(0, 0, i);
+#pragma unroll
+  for (int d = 1; d < PF; ++d) touch(d);
   __builtin_amdgcn_s_waitcnt(0);  // vmcnt = 0: the loads have written LDS
   zero_tail(0);
   __syncthreads();
@@ -197,28 +231,76 @@ __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) vo
   const int y16 = 16 * (hf ^ ((lq >> 1) & 7));
   const int a_row = (wv * (TV / WV) + lq) * 128;
   const int b_row = TILE_BYTES + (wr * (TR / WR) + lq) * 128;
+  auto read_frags = [&](const unsigned char *st, int kk, bf16x8 (&af)[MV], bf16x8 (&bf)[MR]) {
+    const int off = (32 * kk) ^ y16;
+#pragma unroll
+    for (int i = 0; i < MV; ++i) af[i] = *reinterpret_cast<const bf16x8 *>(st + a_row + i * 32 * 128 + off);
+#pragma unroll
+    for (int j = 0; j < MR; ++j) bf[j] = *reinterpret_cast<const bf16x8 *>(st + b_row + j * 32 * 128 + off);
+  };
+  constexpr int KSTEPS = BK / 16;
   for (int ks = 0; ks < KS; ++ks) {
-    // step ks+1 is fetched into the buffer every wave finished reading before the last barrier
-    if (ks + 1 < KS) {
-#pragma unroll
-      for (int i = 0; i < LPW; ++i) issue(ks + 1, i);
-    }
+    // Step ks+1 is fetched into the buffer every wave finished reading before the
+    // last barrier (the last step fetches itself again, into the idle buffer, so
+    // that the loop body stays free of branches).  Within a k-step the
+    // fragments of the NEXT k-step are read and a share of the global loads is
+    // issued between the matrix instructions of this one.
+    const int kn = min(ks + 1, KS - 1);
     const unsigned char *st = smem + (ks & 1) * STAGE;
+    bf16x8 af[2][MV], bf[2][MR];
+    read_frags(st, 0, af[0], bf[0]);
+    constexpr int NREAD = MV + MR, NMFMA = MV * MR;
+    constexpr int LOADS_PER_K = (NMFMA - NREAD) / 2 > 0 ? (NMFMA - NREAD) / 2 : 1;  // operand-pair loads per k-step, earliest first
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const int off = (32 * kk) ^ y16;
-      bf16x8 af[MV], bf[MR];
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      const int cur = kk & 1;
+      if (kk + 1 < KSTEPS) read_frags(st, kk + 1, af[cur ^ 1], bf[cur ^ 1]);
 #pragma unroll
-      for (int i = 0; i < MV; ++i) af[i] = *reinterpret_cast<const bf16x8 *>(st + a_row + i * 32 * 128 + off);
-#pragma unroll
-      for (int j = 0; j < MR; ++j) bf[j] = *reinterpret_cast<const bf16x8 *>(st + b_row + j * 32 * 128 + off);
+      for (int i = kk * LOADS_PER_K; i < (kk + 1) * LOADS_PER_K && i < LPW; ++i) issue(kn, (ks + 1) & 1, i);
 #pragma unroll
       for (int i = 0; i < MV; ++i)
 #pragma unroll
         for (int j = 0; j < MR; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bf[cur][j], acc[i][j], 0, 0, 0);
     }
-    __builtin_amdgcn_s_waitcnt(0);  // this wave's share of step ks+1 is in LDS
+    // Issue order of the whole step (one scheduling region): the first k-step's
+    // fragment reads; then, per k-step, after each matrix instruction one LDS read
+    // (fragments of the next k-step) or one global load.  The global loads all go
+    // out in the first k-steps so that they have the rest of the step to land.
+    {
+      static_assert(KSTEPS * LOADS_PER_K >= LPW, "all loads of a step fit into its k-steps");
+      __builtin_amdgcn_sched_group_barrier(0x100, NREAD, 0);
+#pragma unroll
+      for (int kk = 0; kk < KSTEPS; ++kk) {
+        const bool reads = kk + 1 < KSTEPS;
+        const int first = kk * LOADS_PER_K;
+        const int nl = first >= LPW ? 0 : (LPW - first < LOADS_PER_K ? LPW - first : LOADS_PER_K);
+        if (reads) {
+#pragma unroll
+          for (int q = 0; q < NREAD; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < 2 * nl; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        // the remaining matrix instructions of the k-step, one group each (sizes must be literals)
+#pragma unroll
+        for (int q = (reads ? NREAD : 0) + 2 * nl; q < NMFMA; ++q) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      }
+    }
+    if constexpr (PF > 0) {
+      // the touches go out last, and the wait below leaves exactly them in flight
+      // (memory instructions complete in order)
+      __builtin_amdgcn_sched_barrier(0);
+      touch(ks + PF);
+      __builtin_amdgcn_s_waitcnt(0x0F70 | PFI);  // vmcnt <= PFI: this wave's share of step ks+1 is in LDS
+    } else {
+      __builtin_amdgcn_s_waitcnt(0);  // this wave's share of step ks+1 is in LDS
+    }
     zero_tail(ks + 1);
     __syncthreads();
   }
@@ -228,6 +310,7 @@ __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) vo
   // (increasing in (i, r)) and row = r0 + wr*(TR/WR) + 32 j + lq.
   const int vbase = v0 + wv * (TV / WV) + 4 * hf;
   const bool ragged = v0 + TV > a.V;
+  if constexpr (PF > 0) __builtin_amdgcn_s_waitcnt(0x0F70);  // the last touches have landed
   Partial *lds_part = reinterpret_cast<Partial *>(smem);  // [TR][WV] after the last barrier
 #pragma unroll
   for (int j = 0; j < MR; ++j) {
@@ -295,10 +378,10 @@ __global__ __launch_bounds__(256) void lm_head_finish_kernel(const Partial *__re
   }
 }
 
-template <int WV, int WR>
+template <int WV, int WR, int PF>
 int32_t launch_lm_head_t(const LmArgs &a, int64_t nwg, hipStream_t st) {
-  const size_t lds = 2 * size_t(STAGE);  // two K steps in LDS
-  auto kern = lm_head_kernel<WV, WR>;
+  const size_t lds = 2 * size_t(STAGE) + 2048;  // two K steps in LDS + landing area of the touches
+  auto kern = lm_head_kernel<WV, WR, PF>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -314,9 +397,18 @@ int32_t launch_lm_head_t(const LmArgs &a, int64_t nwg, hipStream_t st) {
 int32_t launch_lm_head(const LmArgs &a, int64_t nwg, hipStream_t st) {
 #ifdef LSP_TUNE
   const char *v = getenv("LSP_LM_VARIANT");
-  if (v && atoi(v) == 1) return launch_lm_head_t<2, 2>(a, nwg, st);
+  const int var = v ? atoi(v) : 0;
+  if (var == 1) return launch_lm_head_t<2, 4, 0>(a, nwg, st);
+  if (var == 2) return launch_lm_head_t<2, 4, 2>(a, nwg, st);
+  if (var == 3) return launch_lm_head_t<2, 2, 2>(a, nwg, st);
 #endif
-  return launch_lm_head_t<2, 4>(a, nwg, st);
+  // Four waves of 128 x 128 outputs each need the fewest LDS reads per matrix
+  // instruction (8 fragment reads feed 16 instructions; eight waves of 128 x 64
+  // need 6 for 8) and win once several row tiles share every weight tile.  With
+  // few rows the weight matrix streams from HBM once and nothing is re-used: two
+  // waves per SIMD then cover the longer load latency better (measured).
+  if (a.RT >= 4) return launch_lm_head_t<2, 2, 0>(a, nwg, st);
+  return launch_lm_head_t<2, 4, 0>(a, nwg, st);
 }
 
 }  // namespace

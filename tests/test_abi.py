@@ -70,6 +70,20 @@ def test_argument_errors_are_reported_before_any_launch():
     args = [sixteen] * 5 + [sixteen, sixteen, sixteen, None, ctypes.c_size_t(0), None]
     assert L.lsp_attn_step(ctypes.byref(d), *args) == -2 and b"head_dim" in L.lsp_last_error()
 
+    # output head: dtype, K granularity, strides, workspace (all before any launch)
+    i64 = ctypes.c_int64
+    def lm(dtype=1, K=64, V=8, hrs=0, wrs=0, ws=sixteen, wsb=1 << 20, hid=sixteen):
+        return L.lsp_lm_head_confidence(dtype, hid, sixteen, 1, 4, K, V, i64(hrs), i64(0), i64(wrs), None,
+                                        p, p, p, ws, ctypes.c_size_t(wsb), None)
+    assert lm(dtype=0) == -2 and b"bf16" in L.lsp_last_error()
+    assert lm(K=60) == -1 and b"multiple of 8" in L.lsp_last_error()
+    assert lm(V=1) == -1
+    assert lm(hrs=32) == -1 and b"strides" in L.lsp_last_error()
+    assert lm(wrs=68) == -1 and b"strides" in L.lsp_last_error()
+    assert lm(hid=ctypes.c_void_p(sixteen.value + 2)) == -1 and b"aligned" in L.lsp_last_error()
+    assert lm(ws=None) == -3 and lm(wsb=8) == -3 and b"workspace" in L.lsp_last_error()
+    assert L.lsp_lm_head_confidence_workspace_bytes(2, 300, 1000) == 2 * 300 * 4 * 16
+
 
 def test_missing_library_fails_loudly(monkeypatch):
     import paper_2603_05454_amd as lsp
