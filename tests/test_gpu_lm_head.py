@@ -113,3 +113,25 @@ def test_c2_shape_sampled_rows(lsp, oracle):
     _compare(sub, ref[:3], ref[3])
     # planted ids of the strongly boosted early rows come out (a property that holds at any size)
     assert torch.equal(got[0][0, :32].long(), info["planted_id"][0, :32].cpu())
+
+
+def test_c4_shape_sampled_rows_and_tile_invariants(lsp, oracle):
+    """Config-4 rows (8 x 1024) in the launch shape the benchmark times (four-wave
+    tiles, 32 row tiles): the oracle evaluates sampled rows from first, middle and
+    last row tiles; every row must also satisfy what holds at any size."""
+    w = W.C4
+    hidden, weight, info = W.make_lm_head(w, 4096, device="cuda")
+    sl = torch.tensor([1024, 1000, 1, 0, 512, 1024, 257, 1024], dtype=torch.int32)
+    got = _run(lsp, hidden, weight, sl)
+    ids, p, m = got
+    act = torch.arange(w.S).view(1, -1) < sl.view(-1, 1)
+    assert torch.all(ids[~act] == -7) and torch.all(m[~act] == -7.0)
+    assert ((ids[act] >= 0) & (ids[act] < w.V)).all() and (m[act] >= 0).all()
+    assert ((p[act] > 0) & (p[act] <= 1.0 + 1e-6)).all()
+    # a probability above one half needs a positive margin: exp(-margin) <= (1 - p) / p
+    assert (torch.exp(-m[act].double()) <= (1 - p[act].double()) / p[act].double() + 1e-4).all()
+    weight_cpu = weight.cpu()
+    for b, rows in ((0, [0, 255, 256, 1023]), (2, [0]), (6, [100, 256])):
+        r = torch.tensor(rows)
+        ref = oracle.lm_head_confidence(hidden[b:b + 1, r].cpu(), weight_cpu, return_logits=True)
+        _compare(tuple(t[b:b + 1, r] for t in got), ref[:3], ref[3])
