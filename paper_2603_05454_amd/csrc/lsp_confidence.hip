@@ -15,8 +15,8 @@
 //     re-read once at the end - by the lanes that hold the wave's maximum only
 //     (every lane doing so would add 16 KB of scattered cache lines per wave);
 //   - the soft-max sum uses one exp2 per element against a lagging per-lane
-//     reference r which is only moved when the lane maximum has run more than
-//     22 units (about 32 octaves) ahead of it, so the rescale branch is cold.  A
+//     reference r (log2 domain) which is only moved when the lane maximum has
+//     run more than 32 octaves ahead of it, so the rescale branch is cold.  A
 //     group's top-2 pass runs before its sum pass, so the reference always
 //     covers the values being exponentiated.
 // Lane results are merged in two steps: the maximum first (DPP reduction), then
@@ -38,12 +38,12 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLag = 22.0f;  // the reference may lag the maximum by this much (about 32 octaves)
+constexpr float kLagOctaves = 32.0f;  // the reference may lag the maximum by this much
 
 struct Top {
   float m1, m2;  // largest and second largest value seen (duplicates count)
-  float s;       // sum of exp(x - r)
-  float r;       // reference value (a logit; the subtraction x - r is exact for the terms that matter)
+  float s;       // sum of exp2(x*log2e - r)
+  float r;       // reference exponent (log2 domain): some earlier maximum times log2e, ROUNDED
   int idx;       // >= 0: element index of the first maximum; < 0: ~(first element of the lane's group holding it)
 };
 
@@ -76,9 +76,9 @@ __device__ __forceinline__ void absorb_top2(Top &t, const float (&x)[N]) {
 
 // Move the reference up when the maximum has run ahead of it (cold branch).
 __device__ __forceinline__ void settle_reference(Top &t) {
-  const float mc = t.m1;
-  if (mc - t.r > kLag) {
-    t.s *= __builtin_amdgcn_exp2f((t.r - mc) * kLog2e);
+  const float mc = t.m1 * kLog2e;
+  if (mc - t.r > kLagOctaves) {
+    t.s *= __builtin_amdgcn_exp2f(t.r - mc);
     t.r = mc;
   }
 }
@@ -86,12 +86,13 @@ __device__ __forceinline__ void settle_reference(Top &t) {
 // Soft-max sum over N values that are already covered by t.m1 / t.r.
 template <int N>
 __device__ __forceinline__ void absorb_sum(Top &t, const float (&x)[N]) {
-  // x - r first: exact for values near the reference, which carry the sum.  (With
-  // fma(x, log2e, -r*log2e) the rounding of r*log2e shows up as a relative error
-  // of |r| * 4e-8 in every term: 2e-5 for logits around 500.)
-  const float r = t.r;
+  // One fma + exp2 per element.  r is a ROUNDED product, so every term is off by
+  // the same factor 2^(m*log2e - r) (up to 2e-5 for logits around 500); the fold
+  // in wave_combine takes the sum off this reference with an fma of its own,
+  // which removes that factor exactly.
+  const float nr = -t.r;
 #pragma unroll
-  for (int j = 0; j < N; ++j) t.s += __builtin_amdgcn_exp2f((x[j] - r) * kLog2e);
+  for (int j = 0; j < N; ++j) t.s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[j], kLog2e, nr));
 }
 
 template <int N>
@@ -165,10 +166,11 @@ struct RowStat {  // wave-uniform: maximum, second, sum of exp(x - m1), first in
   int idx;
 };
 
-// Combine the 64 lane states of a wave, given the maximum over the lanes.  Every
-// lane rescales its own sum to that maximum, so the remaining reductions are
-// plain max/add/min.  A lane's idx is only read when the lane holds the maximum.
-__device__ __forceinline__ RowStat wave_combine(const Top &t, float wave_max) {
+// Combine the 64 lane states of a wave, given the maximum over the lanes and the
+// factor w that takes this lane's sum from its own reference to that maximum.
+// The remaining reductions are plain max/add/min.  A lane's idx is only read
+// when the lane holds the maximum.
+__device__ __forceinline__ RowStat wave_combine(const Top &t, float wave_max, float w) {
   RowStat o;
   o.m1 = wave_max;
   const bool top = t.m1 == o.m1;
@@ -176,7 +178,6 @@ __device__ __forceinline__ RowStat wave_combine(const Top &t, float wave_max) {
   const float second = wave_reduce(top ? t.m2 : t.m1, OpMax());
   o.m2 = ntop >= 2 ? o.m1 : second;  // the maximum held by two lanes is its own runner-up
   o.idx = __float_as_int(wave_reduce(__int_as_float(top ? t.idx : INT_MAX), OpMinI()));
-  const float w = __builtin_amdgcn_exp2f((t.r - o.m1) * kLog2e);  // 0 for an empty lane (r = -FLT_MAX)
   const float sum = wave_reduce(t.s * w, OpAdd());
   o.s = o.m1 == -INFINITY ? 0.f : sum;  // an all -inf segment has an empty sum
   return o;
@@ -300,7 +301,8 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
     t.idx = found;
   }
 
-  RowStat r = wave_combine(t, wave_max);
+  // exp2(r - max*log2e) with the product unrounded inside the fma; 0 for an empty lane (r = -FLT_MAX)
+  RowStat r = wave_combine(t, wave_max, __builtin_amdgcn_exp2f(__builtin_fmaf(-wave_max, kLog2e, t.r)));
   constexpr int NW = NT / kWave;
   if (NW > 1) {
     __shared__ RowStat lds[NW];
@@ -312,9 +314,10 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
     if (lane < NW) {
       const RowStat w = lds[lane];
       t.m1 = w.m1; t.m2 = w.m2; t.s = w.s; t.idx = w.idx;
-      t.r = w.m1 == -INFINITY ? -FLT_MAX : w.m1;
     }
-    r = wave_combine(t, wave_reduce(t.m1, OpMax()));
+    // a wave's sum is relative to that wave's own maximum: exp((m1 - max)), 0 for the lanes beyond NW
+    const float all_max = wave_reduce(t.m1, OpMax());
+    r = wave_combine(t, all_max, __builtin_amdgcn_exp2f((t.m1 - all_max) * kLog2e));
   }
   if (tid != 0) return;
   const int64_t o = int64_t(b) * S + i;
