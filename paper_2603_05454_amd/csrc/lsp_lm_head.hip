@@ -326,12 +326,17 @@ __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) vo
         m2 = fmed3_raw(m1, m2, x);
         m1 = fmax_raw(m1, x);
       }
+    // sum of exp2(z*log2e - rc) against the ROUNDED product rc = m1*log2e (one fma +
+    // exp2 per logit), then taken off that reference with an fma of its own, which
+    // cancels the rounding of rc exactly
     const float ref = m1 == -INFINITY ? 0.f : m1;
+    const float rc = ref * kLog2e;
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < MV; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f((acc[i][j][r] - ref) * kLog2e);
+      for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][r], kLog2e, -rc));
+    s *= __builtin_amdgcn_exp2f(__builtin_fmaf(-ref, kLog2e, rc));
     Partial p;
     p.m1 = m1; p.m2 = m2; p.s = s;
     p.idx = vbase + 32 * (code >> 4) + 8 * ((code & 15) >> 2) + (code & 3);
