@@ -61,6 +61,9 @@ def parse():
                     help="1: run lsp_attn_step on a second stream beside lsp_confidence (measured: the two "
                          "cross-stream joins per step cost more than the overlap gains at c2, and gain <1%% at c4)")
     ap.add_argument("--graph", type=int, default=1, help="replay the step from a HIP graph (1) or launch eagerly (0)")
+    ap.add_argument("--loop-graph", type=int, default=0,
+                    help="c5: replay every step after the first from one captured HIP graph (measured: no faster than "
+                         "eager launches, the loop is bound by the attention kernels)")
     return ap.parse_args()
 
 
@@ -294,7 +297,7 @@ def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True, overl
     return value, ms_per_step, config, roofline, cpu
 
 
-def run_loop_workload(max_steps=0, sizing="tau"):
+def run_loop_workload(max_steps=0, sizing="tau", use_graph=True):
     """Config 5: the whole decode loop (Algorithm 1 lines 3-11) at LLaDA-8B shape, batch 16,
     prompt 512, 1024 generated positions, all 32 layers' attention and KV append every step.
     The step's logits come from the seeded synthetic process (workloads.make_process_logits),
@@ -324,7 +327,7 @@ def run_loop_workload(max_steps=0, sizing="tau"):
     t0 = time.perf_counter()
     r = decode_loop(fn, bitmap.to(dev), w.V, tau, w.window, w.min_commit, 1, pl, sl, tokens,
                     kv_layers=layers, gen_len=w.gen_len, run_attention=True, timed=True,
-                    stop_after=max_steps or None, commit_kw=kw)
+                    stop_after=max_steps or None, commit_kw=kw, graph=use_graph)
     wall = time.perf_counter() - t0
     lsp_s = r["lsp_ms"] * 1e-3
     config = {"workload": w.name, "B": w.B, "layers": w.layers, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
@@ -334,7 +337,8 @@ def run_loop_workload(max_steps=0, sizing="tau"):
               "ms_at_steps": {str(i): round(r["lsp_ms_steps"][i], 3)
                               for i in sorted({0, 1, r["steps"] // 4, r["steps"] // 2, 3 * r["steps"] // 4, r["steps"] - 1})},
               "lsp_seconds": round(lsp_s, 4), "wall_seconds_with_logit_generator": round(wall, 2),
-              "launch": "eager, one termination poll per step", "dtype": w.dtype}
+              "launch": ("first step eager, then one HIP graph replayed per step" if use_graph else "eager") +
+                        ", one termination poll per step", "dtype": w.dtype}
     return r["committed"] / lsp_s, r["lsp_ms"] / max(1, r["steps"]), config
 
 
@@ -500,7 +504,7 @@ def main():
                           "n_gpus": 1, "dtype": "bf16", "data": "synthetic", **run_lm_head_comparison()}))
         return
     if args.workload == "c5":
-        value, ms, config = run_loop_workload(args.loop_steps, args.sizing)
+        value, ms, config = run_loop_workload(args.loop_steps, args.sizing, use_graph=bool(args.loop_graph))
         print(json.dumps({"metric": "committed tokens/sec + per-step latency (ms), LLaDA-8B shape, 1 MI355X",
                           "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": config["loop_steps"],
                           "warmup": 0, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",

@@ -179,6 +179,7 @@ __device__ __forceinline__ void softmax_pv(f32x16 &s, f32x16 (&oacc)[D / 32], fl
 // spread over all of them, and the tiles of one unit still run close enough
 // together to share its K/V stream in L2.
 constexpr int kUnitGroup = 8;
+constexpr int kShortSuffix = 64;  // sequences with at most this many active rows take the key-split kernel
 struct Place {
   int b, g, h, q0;
   bool valid;
@@ -292,7 +293,9 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
   const Place pl = place(a, 32 * WM);
   if (!pl.valid) return;
   const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
-  const int N = min(max(a.suffix_len[b], 0), a.S);
+  const int nb = a.suffix_len[b];
+  if (nb <= a.n_min || nb > a.n_max) return;  // another launch serves this sequence
+  const int N = min(max(nb, 0), a.S);
   if (q0 >= N) return;
   const int P = min(max(a.prefix_len[b], 0), a.C);
   const int T = P + N;
@@ -435,7 +438,9 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
   const Place pl = place(a, 32 * WM);
   if (!pl.valid) return;
   const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
-  const int N = min(max(a.suffix_len[b], 0), a.S);
+  const int nb = a.suffix_len[b];
+  if (nb <= a.n_min || nb > a.n_max) return;  // another launch serves this sequence
+  const int N = min(max(nb, 0), a.S);
   if (q0 >= N) return;
   const int P = min(max(a.prefix_len[b], 0), a.C);
   const int T = P + N;
@@ -611,10 +616,26 @@ int32_t dispatch(const AttnArgs &a, hipStream_t st) {
   // Otherwise the wave-private kernel with the key range split between waves.
   const int64_t rows = int64_t(a.B) * a.Hq * a.S;  // upper bound on (b,h,row) triples
   if (rows / 128 >= 256) {
-    if constexpr (D == 128) {
-      if (a.S > 128) return launch_tile<D, 8, 2, 6>(a, st);
+    // Sequences whose suffix has shrunk to a few rows (the late steps of a decode
+    // loop) would each keep one wide tile busy for the whole key range with most
+    // of its queries masked; they are served by a second launch of the
+    // wave-private kernel, which splits the KEY range over eight waves instead.
+    // Lengths live in device memory, so both launches always go out and every
+    // workgroup looks up which of the two its sequence belongs to.
+    AttnArgs lo = a, hi = a;
+    if (a.S > kShortSuffix) {
+      hi.n_min = kShortSuffix;
+      lo.n_max = kShortSuffix;
+      lo.S = kShortSuffix;
     }
-    return launch_tile<D, 4, 2, 4>(a, st);
+    int32_t rc;
+    if constexpr (D == 128) {
+      rc = a.S > 128 ? launch_tile<D, 8, 2, 6>(hi, st) : launch_tile<D, 4, 2, 4>(hi, st);
+    } else {
+      rc = launch_tile<D, 4, 2, 4>(hi, st);
+    }
+    if (rc != LSP_OK || a.S <= kShortSuffix) return rc;
+    return launch<D, 1, 8>(lo, st);
   }
   if (rows / 64 >= 512) return launch<D, 2, 2>(a, st);
   if (rows / 32 >= 512) return launch<D, 1, 4>(a, st);

@@ -15,7 +15,8 @@ from . import LayerTable, attn_step, commit, confidence, flip_update
 
 def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
                 prefix_len, suffix_len, tokens, kv_layers=None, gen_len=None, run_attention=False,
-                poll=1, max_steps=100000, stop_after=None, observer=None, timed=False, commit_kw=None):
+                poll=1, max_steps=100000, stop_after=None, observer=None, timed=False, commit_kw=None,
+                graph=False):
     """logits_fn(step, prefix_len) -> device logits [B,S,V].  prefix_len,
     suffix_len, tokens and the caches in kv_layers (list of dicts q?, k_suf,
     v_suf, k_cache, v_cache) are updated in place.
@@ -25,6 +26,11 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     (the tensors are reused by the next step: copy what is to be kept).
     timed: bracket every step's library calls with HIP events on the current
     stream and return their sum as lsp_ms (the logits callback is outside).
+    graph: launch every step after the first from ONE captured HIP graph (all
+    sequence state lives in device memory and no entry point reads it on the
+    host, so the same graph serves every step); the first step runs eagerly.
+    The step's logits must then sit at one address: a tensor that logits_fn
+    returns elsewhere is copied there (outside the timed region).
     Returns dict(steps, flips, flip_denominator, committed[, lsp_ms, lsp_ms_steps])."""
     dev = prefix_len.device
     B = prefix_len.shape[0]
@@ -40,16 +46,10 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     out = conf = None
     attn_out = None
     events = []
-    while True:
-        if steps % poll == 0 and int(suffix_len.max().item()) == 0:
-            break
-        if stop_after is not None and steps >= stop_after:
-            break
-        assert steps < max_steps
-        z = logits_fn(steps, prefix_len)
-        if timed:
-            events.append((torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)))
-            events[-1][0].record()
+    zbuf = step_graph = None
+
+    def one_step(z):
+        nonlocal out, conf, attn_out
         if run_attention and kv_layers is not None:
             for L in kv_layers:
                 attn_out = attn_step(L["q"], L["k_suf"], L["v_suf"], L["k_cache"], L["v_cache"],
@@ -59,6 +59,31 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
         out = commit(conf[2], conf[0], bitmap, V, tau, window, min_commit, snap_enabled,
                      prefix_len, suffix_len, tokens=tokens, layers=table, C=tokens.shape[1], out=out,
                      **(commit_kw or {}))
+
+    while True:
+        if steps % poll == 0 and int(suffix_len.max().item()) == 0:
+            break
+        if stop_after is not None and steps >= stop_after:
+            break
+        assert steps < max_steps
+        z = logits_fn(steps, prefix_len)
+        if graph:
+            if zbuf is None:
+                zbuf = z
+            elif z.data_ptr() != zbuf.data_ptr():
+                zbuf.copy_(z)
+                z = zbuf
+        if graph and steps >= 1 and step_graph is None:   # one-time set-up, not part of a step
+            step_graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(step_graph):
+                one_step(zbuf)
+        if timed:
+            events.append((torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)))
+            events[-1][0].record()
+        if graph and steps >= 1:
+            step_graph.replay()
+        else:
+            one_step(z)
         if timed:
             events[-1][1].record()
         if observer is not None:

@@ -157,6 +157,25 @@ def test_many_rows_ragged_lengths_sampled(lsp, oracle, D, Hq, Hkv, S):
         assert not torch.isnan(got[b, : int(sl[b])]).any()
 
 
+def test_mixed_short_and_long_suffixes_in_one_call(lsp, oracle):
+    """At the long-suffix launch shape the sequences whose suffix is down to a few
+    rows are served by a second launch (key range split between waves): lengths on
+    both sides of that split, in one call, every active row against the oracle."""
+    w = W.scaled(W.C2, B=8, S=320, P=200, C=256, Hq=16, Hkv=4, D=128, seed=77)
+    pl = torch.tensor([200, 256, 0, 31, 200, 97, 256, 5], dtype=torch.int32)
+    sl = torch.tensor([0, 1, 33, 64, 65, 200, 320, 31], dtype=torch.int32)
+    kv = W.make_layer_kv(w, 0, prefix_len=pl)
+    got = _run(lsp, kv, pl, sl)
+    rows = torch.tensor([[b, i, h] for b in range(w.B) for i in range(int(sl[b])) for h in (0, 5, 15)
+                         if i < 3 or i >= int(sl[b]) - 3 or i % 29 == 0], dtype=torch.int32)
+    ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl, rows=rows)
+    sel = got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()]
+    assert (sel - ref).abs().max().item() <= 2e-2
+    for b in range(w.B):
+        assert torch.all(got[b, int(sl[b]):] == 123.0)
+        assert not torch.isnan(got[b, : int(sl[b])]).any()
+
+
 def test_strided_views_many_rows_sampled(lsp, oracle):
     """Q/K/V sliced out of one fused [B,S,Hq+2Hkv,D] buffer and a cache with padded
     rows, at a size that takes the long-suffix launch shape."""

@@ -17,10 +17,14 @@ def lsp():
     return m
 
 
+@pytest.mark.parametrize("graph", [False, True])
 @pytest.mark.parametrize("tau,Lmin,sizing", [(0.9, 1, {}), (float("inf"), 3, {}),
                                              (0.9, 1, dict(adaptive=True, alpha=0.25, beta=0.5)),
                                              (-float("inf"), 1, dict(max_commit=8))])
-def test_small_loop_matches_oracle(lsp, oracle, tau, Lmin, sizing):
+def test_small_loop_matches_oracle(lsp, oracle, tau, Lmin, sizing, graph):
+    """graph=True: every step after the first is a replay of ONE captured HIP graph
+    (with this loop's own eager work - the logits generator, the copy into the
+    captured buffer, the termination poll - between the replays)."""
     from paper_2603_05454_amd.loop import decode_loop as gpu_loop
     G = 96
     w = W.scaled(W.C5, B=3, S=G, V=4096, P=16, gen_len=G, C=16 + G, layers=2, Hq=2, Hkv=2, D=64)
@@ -36,7 +40,7 @@ def test_small_loop_matches_oracle(lsp, oracle, tau, Lmin, sizing):
     tok_g = W.make_tokens(w, w.C).cuda()
     lay_g = [{k: v.cuda() for k, v in W.make_layer_kv(w, l).items()} for l in range(2)]
     got = gpu_loop(lambda s, p: fn(s, p).cuda(), bm.cuda(), w.V, tau, w.window, Lmin, 1, pl_g, sl_g, tok_g,
-                   kv_layers=lay_g, gen_len=G, commit_kw=sizing)
+                   kv_layers=lay_g, gen_len=G, commit_kw=sizing, run_attention=graph, graph=graph)
     assert (got["steps"], got["flips"], got["flip_denominator"], got["committed"]) == \
            (ref["steps"], ref["flips"], ref["flip_denominator"], ref["committed"])
     assert torch.equal(tok_g.cpu(), tokens) and torch.equal(pl_g.cpu(), pl) and torch.equal(sl_g.cpu(), sl)
