@@ -113,16 +113,8 @@ __device__ __forceinline__ void load_to_lds(const char *g, unsigned char *lds_ba
   __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void *)lds_base, 16, 0, 0);
 }
 
-// 4 bytes per lane into LDS (lane l lands at lds_base + 4 l): used only to pull
-// 64 cache lines, one per lane, into L2 ahead of time.
-__device__ __forceinline__ void touch_to_lds(const char *g, unsigned char *lds_base) {
-  __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void *)lds_base, 4, 0, 0);
-}
-
-// WV x WR waves: WV along the vocabulary, WR along the rows.  PF > 0: every
-// step also touches the operand lines of the step PF ahead, so that the real
-// loads, one step ahead, find them in L2.
-template <int WV, int WR, int PF>
+// WV x WR waves: WV along the vocabulary, WR along the rows.
+template <int WV, int WR>
 __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) void lm_head_kernel(LmArgs a) {
   constexpr int NT = 64 * WV * WR;
   constexpr int MV = TV / WV / 32;  // 32x32 blocks per wave along the vocabulary
@@ -173,23 +165,7 @@ __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) vo
     wp[i] = reinterpret_cast<const char *>(a.weight + int64_t(v) * a.wrs) + 16 * chunk[i];
     hp[i] = reinterpret_cast<const char *>(a.hidden + int64_t(r / a.S) * a.hbs + int64_t(r % a.S) * a.hrs) + 16 * chunk[i];
   }
-  // L2 warm-up: a step's operand tiles are 2 x 256 rows x one 128-byte line; eight
-  // wave-wide 4-byte loads with the lanes one row apart touch them all.
-  constexpr int PFI = PF > 0 ? 8 / NW : 0;
-  const char *pfp[PFI > 0 ? PFI : 1];
-#pragma unroll
-  for (int j = 0; j < PFI; ++j) {
-    const int idx = wave + NW * j, row = 64 * (idx & 3) + lane;
-    const int v = min(v0 + row, a.V - 1), r = min(r0 + row, rows - 1);
-    pfp[j] = idx < 4 ? reinterpret_cast<const char *>(a.weight + int64_t(v) * a.wrs)
-                     : reinterpret_cast<const char *>(a.hidden + int64_t(r / a.S) * a.hbs + int64_t(r % a.S) * a.hrs);
-  }
   const int KS = (a.K + BK - 1) / BK;
-  auto touch = [&](int ks) {  // lines of step ks (clamped: the last steps touch the last step again)
-    const int kbyte = min(ks, KS - 1) * BK * 2;
-#pragma unroll
-    for (int j = 0; j < PFI; ++j) touch_to_lds(pfp[j] + kbyte, smem + 2 * STAGE + 256 * (wave_s + NW * j));
-  };
   const int tail_chunks = (a.K % BK) / 8;  // valid 16-byte chunks of a ragged last step (0 = none ragged)
   auto issue = [&](int ks, int buf, int i) {
     unsigned char *st = smem + buf * STAGE + 1024 * (wave_s + NW * i);
@@ -222,8 +198,6 @@ __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) vo
 
 #pragma unroll
   for (int i = 0; i < LPW; ++i) issue(0, 0, i);
-#pragma unroll
-  for (int d = 1; d < PF; ++d) touch(d);
   __builtin_amdgcn_s_waitcnt(0);  // vmcnt = 0: the loads have written LDS
   zero_tail(0);
   __syncthreads();
@@ -292,15 +266,7 @@ __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) vo
         for (int q = (reads ? NREAD : 0) + 2 * nl; q < NMFMA; ++q) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       }
     }
-    if constexpr (PF > 0) {
-      // the touches go out last, and the wait below leaves exactly them in flight
-      // (memory instructions complete in order)
-      __builtin_amdgcn_sched_barrier(0);
-      touch(ks + PF);
-      __builtin_amdgcn_s_waitcnt(0x0F70 | PFI);  // vmcnt <= PFI: this wave's share of step ks+1 is in LDS
-    } else {
-      __builtin_amdgcn_s_waitcnt(0);  // this wave's share of step ks+1 is in LDS
-    }
+    __builtin_amdgcn_s_waitcnt(0);  // this wave's share of step ks+1 is in LDS
     zero_tail(ks + 1);
     __syncthreads();
   }
@@ -310,7 +276,6 @@ __global__ __launch_bounds__(64 * WV * WR, 512 / (64 * WV * WR) >= 2 ? 1 : 2) vo
   // (increasing in (i, r)) and row = r0 + wr*(TR/WR) + 32 j + lq.
   const int vbase = v0 + wv * (TV / WV) + 4 * hf;
   const bool ragged = v0 + TV > a.V;
-  if constexpr (PF > 0) __builtin_amdgcn_s_waitcnt(0x0F70);  // the last touches have landed
   Partial *lds_part = reinterpret_cast<Partial *>(smem);  // [TR][WV] after the last barrier
 #pragma unroll
   for (int j = 0; j < MR; ++j) {
@@ -383,10 +348,10 @@ __global__ __launch_bounds__(256) void lm_head_finish_kernel(const Partial *__re
   }
 }
 
-template <int WV, int WR, int PF>
+template <int WV, int WR>
 int32_t launch_lm_head_t(const LmArgs &a, int64_t nwg, hipStream_t st) {
-  const size_t lds = 2 * size_t(STAGE) + 2048;  // two K steps in LDS + landing area of the touches
-  auto kern = lm_head_kernel<WV, WR, PF>;
+  const size_t lds = 2 * size_t(STAGE);  // two K steps in LDS
+  auto kern = lm_head_kernel<WV, WR>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -402,18 +367,16 @@ int32_t launch_lm_head_t(const LmArgs &a, int64_t nwg, hipStream_t st) {
 int32_t launch_lm_head(const LmArgs &a, int64_t nwg, hipStream_t st) {
 #ifdef LSP_TUNE
   const char *v = getenv("LSP_LM_VARIANT");
-  const int var = v ? atoi(v) : 0;
-  if (var == 1) return launch_lm_head_t<2, 4, 0>(a, nwg, st);
-  if (var == 2) return launch_lm_head_t<2, 4, 2>(a, nwg, st);
-  if (var == 3) return launch_lm_head_t<2, 2, 2>(a, nwg, st);
+  if (v && atoi(v) == 1) return launch_lm_head_t<2, 4>(a, nwg, st);
+  if (v && atoi(v) == 2) return launch_lm_head_t<2, 2>(a, nwg, st);
 #endif
   // Four waves of 128 x 128 outputs each need the fewest LDS reads per matrix
   // instruction (8 fragment reads feed 16 instructions; eight waves of 128 x 64
   // need 6 for 8) and win once several row tiles share every weight tile.  With
   // few rows the weight matrix streams from HBM once and nothing is re-used: two
   // waves per SIMD then cover the longer load latency better (measured).
-  if (a.RT >= 4) return launch_lm_head_t<2, 2, 0>(a, nwg, st);
-  return launch_lm_head_t<2, 4, 0>(a, nwg, st);
+  if (a.RT >= 4) return launch_lm_head_t<2, 2>(a, nwg, st);
+  return launch_lm_head_t<2, 4>(a, nwg, st);
 }
 
 }  // namespace
