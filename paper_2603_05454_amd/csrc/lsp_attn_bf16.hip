@@ -95,15 +95,39 @@ struct Geo {
   static constexpr int WAVE_LDS = KBYTES + VBYTES > OBYTES ? KBYTES + VBYTES : OBYTES;
 };
 
+// V^T fragments of a 32-key block for O^T += V^T . P^T, read from an LDS tile of
+// 32 rows (pitch VPITCH) with the transpose load: within 16 lanes, lane s
+// addresses row (s/4), columns 4*(s%4)..+3 and receives column s of the 4 rows.
+// Contraction slot 8*hf+e of step k2 is key 16*k2 + 8*(e/4) + 4*hf + e%4 (the
+// accumulator row order of the first product).
+template <int D>
+__device__ __forceinline__ void load_v_frags(bf16x8 (&vf)[D / 32][2], int lane, const unsigned char *vtile) {
+  constexpr int VPITCH = Geo<D>::VPITCH;
+  const int hf = lane >> 5, s16 = lane & 15;
+  const unsigned char *vbase = vtile + (4 * hf + (s16 >> 2)) * VPITCH + (16 * ((lane >> 4) & 1) + 4 * (s16 & 3)) * 2;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int k2 = 0; k2 < 2; ++k2) {
+      const unsigned char *ap = vbase + (16 * k2) * VPITCH + 64 * db;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4 *)(ap));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4 *)(ap + 8 * VPITCH));
+      const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+      const u32x4 w = {l2.x, l2.y, h2.x, h2.y};
+      vf[db][k2] = __builtin_bit_cast(bf16x8, w);
+    }
+}
+
 // Second half of a 32-key block, shared by both kernels: soft-max of the score
 // block s (keys key0.., this wave's 32 queries) against the lagging reference,
-// then O^T += V^T . P^T with V read from an LDS tile of 32 rows (pitch VPITCH).
+// then O^T += V^T . P^T with the V^T fragments vf.
 template <int D>
 __device__ __forceinline__ void softmax_pv(f32x16 &s, f32x16 (&oacc)[D / 32], float &mref, float &lsum,
                                            int key0, int T, float sc, int lane,
-                                           const unsigned char *vtile) {
+                                           const bf16x8 (&vf)[D / 32][2]) {
   constexpr int DB = D / 32;
-  constexpr int VPITCH = Geo<D>::VPITCH;
   const int hf = lane >> 5;
   if (key0 + 32 > T) {  // ragged last block: keys >= T get -inf
 #pragma unroll
@@ -143,25 +167,11 @@ __device__ __forceinline__ void softmax_pv(f32x16 &s, f32x16 (&oacc)[D / 32], fl
     w.w = pack_bf16(p[6], p[7]);
     pf[k2] = __builtin_bit_cast(bf16x8, w);
   }
-  // O^T[d, query] += V^T[d, key] . P^T[key, query]; contraction slot 8*hf+e of
-  // step k2 is key 16*k2 + 8*(e/4) + 4*hf + e%4 (the accumulator row order).
-  // Transpose load: within 16 lanes, lane s addresses row (s/4), columns 4*(s%4)..+3
-  // and receives column s of the 4 rows.
-  const int s16 = lane & 15;
-  const unsigned char *vbase = vtile + (4 * hf + (s16 >> 2)) * VPITCH + (16 * ((lane >> 4) & 1) + 4 * (s16 & 3)) * 2;
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int k2 = 0; k2 < 2; ++k2) {
-      const unsigned char *ap = vbase + (16 * k2) * VPITCH + 64 * db;
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4 *)(ap));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4 *)(ap + 8 * VPITCH));
-      const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-      const u32x4 w = {l2.x, l2.y, h2.x, h2.y};
-      oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), pf[k2], oacc[db], 0, 0, 0);
-    }
+    for (int k2 = 0; k2 < 2; ++k2)
+      oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][k2], pf[k2], oacc[db], 0, 0, 0);
 }
 
 // Workgroup placement shared by both kernels.  Workgroups are handed to the 8
@@ -363,7 +373,9 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
       const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(wlds + lq * G::KPITCH + (16 * kk + 8 * hf) * 2);
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
     }
-    softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, wlds + G::KBYTES);
+    bf16x8 vf[DB][2];
+    load_v_frags<D>(vf, lane, wlds + G::KBYTES);
+    softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, vf);
   };
 
   if (wk < NB) load_kv(wk);
@@ -543,19 +555,28 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
       const int jb = jb0 + u;
       if (jb >= NB) break;
       // block jb+1 (register set u) goes into the stage that every wave finished
-      // reading before the last barrier; the set is refilled with block jb+1+PD
+      // reading before the last barrier; the set is refilled with block jb+1+PD.
+      // Issue order of a block: all K fragment reads; the staging traffic of the
+      // blocks ahead (which covers the reads' latency); the first product; all
+      // V^T fragment reads (they land while the chain of the first product and
+      // the exponentials run); soft-max; second product.
+      const unsigned char *st = smem + (jb & 1) * TG::STAGE;
+      bf16x8 kf[KK];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        kf[kk] = *reinterpret_cast<const bf16x8 *>(st + lq * TG::KPITCH + (16 * kk + 8 * hf) * 2);
+      __builtin_amdgcn_sched_barrier(0);
       if (jb + 1 < NB) store_block(jb + 1, kreg[u], vreg[u]);
       if (jb + 1 + PD < NB) load_block(jb + 1 + PD, kreg[u], vreg[u]);
-      const unsigned char *st = smem + (jb & 1) * TG::STAGE;
       f32x16 s;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + lq * TG::KPITCH + (16 * kk + 8 * hf) * 2);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
-      }
-      softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, st + TG::KBYTES);
+      for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
+      bf16x8 vf[DB][2];
+      load_v_frags<D>(vf, lane, st + TG::KBYTES);
+      __builtin_amdgcn_sched_barrier(0);
+      softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, vf);
       __syncthreads();
     }
   }
