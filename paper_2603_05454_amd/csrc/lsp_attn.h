@@ -14,7 +14,6 @@ struct AttnArgs {
   void *workspace;
   int32_t unit_group;  // set by the bf16 launcher: units per placement group
   const int32_t *cache_rows;  // gather form only: key t < P_b of sequence b is cache row cache_rows[b*C + t]; else null
-  int32_t n_min, n_max;       // a launch serves the sequences with n_min < N_b <= n_max (set by the bf16 launcher)
 };
 
 // Cache row that holds key t (t < P_b) of sequence b.

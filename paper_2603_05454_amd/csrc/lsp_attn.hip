@@ -71,8 +71,6 @@ int32_t attn_entry(const lsp_attn_desc *d, const void *q, const void *k_suf, con
   a.prefix_len = prefix_len; a.suffix_len = suffix_len; a.workspace = workspace;
   a.cache_rows = cache_rows;
   a.unit_group = 1;
-  a.n_min = -1;
-  a.n_max = 0x7fffffff;
   hipStream_t st = static_cast<hipStream_t>(stream);
   return d->dtype == LSP_F32 ? launch_attn_f32(a, st) : launch_attn_bf16(a, st);
 }

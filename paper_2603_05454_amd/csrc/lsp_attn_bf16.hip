@@ -291,23 +291,17 @@ __device__ __forceinline__ void merge_store(const AttnArgs &a, const f32x16 (&oa
   }
 }
 
+// Body of the wave-private kernel for the WM*32 queries from q0 of (sequence b,
+// query head h, KV head g); every thread of a workgroup of 64*WM*WK threads
+// calls it with the same arguments (it contains barriers).
 template <int D, int WM, int WK, bool GATHER>
-__global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) {
+__device__ __forceinline__ void key_split_body(const AttnArgs &a, int b, int g, int h, int q0, int N, int P,
+                                               unsigned char *smem) {
   using G = Geo<D>;
   constexpr int KK = D / 16;  // d-steps of the first product
   constexpr int DB = D / 32;  // 32-row blocks of O^T
   constexpr int VL = D / 16;  // 16-byte V loads per lane per block (32 rows * D*2 bytes / 64 lanes / 16)
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const Place pl = place(a, 32 * WM);
-  if (!pl.valid) return;
-  const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
-  const int nb = a.suffix_len[b];
-  if (nb <= a.n_min || nb > a.n_max) return;  // another launch serves this sequence
-  const int N = min(max(nb, 0), a.S);
-  if (q0 >= N) return;
-  const int P = min(max(a.prefix_len[b], 0), a.C);
   const int T = P + N;
   const int wm = wave / WK, wk = wave % WK;
   const int lq = lane & 31, hf = lane >> 5;
@@ -406,6 +400,17 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
 }
 
 template <int D, int WM, int WK, bool GATHER>
+__global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const Place pl = place(a, 32 * WM);
+  if (!pl.valid) return;
+  const int N = min(max(a.suffix_len[pl.b], 0), a.S);
+  if (pl.q0 >= N) return;
+  const int P = min(max(a.prefix_len[pl.b], 0), a.C);
+  key_split_body<D, WM, WK, GATHER>(a, pl.b, pl.g, pl.h, pl.q0, N, P, smem);
+}
+
+template <int D, int WM, int WK, bool GATHER>
 int32_t launch_g(AttnArgs a, hipStream_t st) {
   const int64_t nwg = place_grid(a, 32 * WM);
   if (nwg > 0x7fffffff) {
@@ -450,11 +455,24 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
   const Place pl = place(a, 32 * WM);
   if (!pl.valid) return;
   const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
-  const int nb = a.suffix_len[b];
-  if (nb <= a.n_min || nb > a.n_max) return;  // another launch serves this sequence
-  const int N = min(max(nb, 0), a.S);
-  if (q0 >= N) return;
+  const int N = min(max(a.suffix_len[b], 0), a.S);
   const int P = min(max(a.prefix_len[b], 0), a.C);
+  // A sequence whose suffix is down to a few rows (the late steps of a decode
+  // loop) would keep this wide tile busy for the whole key range with most of
+  // its queries masked.  Its first tiles then each take ONE block of 32 queries
+  // and split the KEY range between their waves instead.  Lengths live in device
+  // memory, so the choice is made here, per workgroup, not by the launcher.
+  // (Only the eight-wave form: it owns its compute unit anyway, so the larger LDS
+  // footprint of the key-split mode costs no occupancy.)
+  if constexpr (WM == 8) {
+    const int tile = q0 / (32 * WM), QT = (a.S + 32 * WM - 1) / (32 * WM);
+    const int short_rows = 32 * min(QT, kShortSuffix / 32);
+    if (N <= short_rows) {
+      if (32 * tile < N) key_split_body<D, 1, WM, GATHER>(a, b, g, h, 32 * tile, N, P, smem);
+      return;
+    }
+  }
+  if (q0 >= N) return;
   const int T = P + N;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 31, hf = lane >> 5;
@@ -606,7 +624,10 @@ int32_t launch_tile_g(AttnArgs a, hipStream_t st) {
     set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
     return LSP_ERR_UNSUPPORTED;
   }
-  const size_t lds = 2 * size_t(TileGeo<D>::STAGE);
+  // two shared stages, or the key-split mode's WM wave regions + 32 Q rows
+  const size_t lds_tile = 2 * size_t(TileGeo<D>::STAGE);
+  const size_t lds_split = WM == 8 ? size_t(WM) * Geo<D>::WAVE_LDS + 32 * size_t(Geo<D>::KPITCH) : 0;
+  const size_t lds = lds_tile > lds_split ? lds_tile : lds_split;
   auto kern = attn_bf16_tile_kernel<D, WM, OCC, PD, GATHER>;
   static bool configured = false;  // per instantiation
   if (!configured) {
@@ -637,26 +658,10 @@ int32_t dispatch(const AttnArgs &a, hipStream_t st) {
   // Otherwise the wave-private kernel with the key range split between waves.
   const int64_t rows = int64_t(a.B) * a.Hq * a.S;  // upper bound on (b,h,row) triples
   if (rows / 128 >= 256) {
-    // Sequences whose suffix has shrunk to a few rows (the late steps of a decode
-    // loop) would each keep one wide tile busy for the whole key range with most
-    // of its queries masked; they are served by a second launch of the
-    // wave-private kernel, which splits the KEY range over eight waves instead.
-    // Lengths live in device memory, so both launches always go out and every
-    // workgroup looks up which of the two its sequence belongs to.
-    AttnArgs lo = a, hi = a;
-    if (a.S > kShortSuffix) {
-      hi.n_min = kShortSuffix;
-      lo.n_max = kShortSuffix;
-      lo.S = kShortSuffix;
-    }
-    int32_t rc;
     if constexpr (D == 128) {
-      rc = a.S > 128 ? launch_tile<D, 8, 2, 6>(hi, st) : launch_tile<D, 4, 2, 4>(hi, st);
-    } else {
-      rc = launch_tile<D, 4, 2, 4>(hi, st);
+      if (a.S > 128) return launch_tile<D, 8, 2, 6>(a, st);
     }
-    if (rc != LSP_OK || a.S <= kShortSuffix) return rc;
-    return launch<D, 1, 8>(lo, st);
+    return launch_tile<D, 4, 2, 4>(a, st);
   }
   if (rows / 64 >= 512) return launch<D, 2, 2>(a, st);
   if (rows / 32 >= 512) return launch<D, 1, 4>(a, st);
