@@ -190,6 +190,7 @@ size_t lsp_commit_workspace_bytes(const lsp_commit_desc *desc);
  * int32[B] in/out.  stable_mask: device uint8 [B,S].  raw_boundary,
  * snapped_boundary, commit_len, status_flags: device int32[B] out
  * (status_flags may be NULL).  tau_used: device fp32[B] out, or NULL.
+ * Limits: B <= 65535, S <= 65536.
  */
 int32_t lsp_commit(const lsp_commit_desc *desc, const float *margin, const int32_t *top1_id,
                    const uint32_t *delimiter_bitmap,

@@ -5,8 +5,11 @@
 // Two kernels.  The boundary kernel runs one workgroup per sequence: every
 // wave ballots "unstable" over its 64 positions, the first set bit of the first
 // non-empty ballot is that wave's candidate, and an LDS minimum across waves
-// gives L'.  The delimiter search walks back from L' through the window with
-// one lane per candidate length and an LDS maximum.  The append kernel then
+// gives L'.  The same pass ballots "predicts a delimiter" per position into
+// LDS words, so the search for the last delimiter inside the window is a scan
+// of a few words (one thread per word, highest set bit, LDS maximum); margins,
+// ids, lengths and bitmap words are all requested up front, which leaves two
+// dependent trips to memory on the critical path.  The append kernel then
 // copies, per (layer, K|V, sequence), the single contiguous block of
 // L * Hkv * D elements from the suffix buffer to cache row P with 16-byte
 // loads and stores; the block length is read from device memory, so the host
@@ -21,6 +24,7 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kScanThreads = 256;
+constexpr int kMaxScanRows = 65536;  // S at most this (one delimiter ballot bit per row in LDS)
 
 __global__ __launch_bounds__(kScanThreads) void boundary_kernel(
     const float *__restrict__ margin, const int32_t *__restrict__ top1_id,
@@ -35,11 +39,27 @@ __global__ __launch_bounds__(kScanThreads) void boundary_kernel(
   const int lane = tid & (kWave - 1);
   __shared__ int s_first, s_snap, s_lo_hit, s_hi_hit;
   __shared__ float s_min[kScanThreads];
-  const int N = min(max(suffix_len[b], 0), S);
-  const int P = max(prefix_len[b], 0);
+  __shared__ unsigned long long s_delim[kMaxScanRows / 64];  // bit i%64 of word i/64: position i predicts a delimiter
   const float *mg = margin + int64_t(b) * S;
   const int32_t *id = top1_id + int64_t(b) * S;
   uint8_t *mk = stable_mask + int64_t(b) * S;
+  // Everything the scan needs is requested before anything is waited for: the
+  // lengths, and this thread's margins and ids (in bounds for every i < S,
+  // whatever N turns out to be).  The delimiter bit of every position is looked
+  // up right away as well, so that the snap search further down is a scan over
+  // ballot words in LDS instead of two more dependent trips to memory.
+  const int nraw = suffix_len[b], praw = prefix_len[b];
+  constexpr int kKeep = 4;  // ids of the first kKeep rounds stay in registers for the token commit
+  int32_t idr[kKeep];
+  float mgr[kKeep];
+#pragma unroll
+  for (int k = 0; k < kKeep; ++k) {
+    const int i = k * kScanThreads + tid;
+    idr[k] = i < S ? id[i] : 0;
+    mgr[k] = i < S ? mg[i] : 0.f;
+  }
+  const int N = min(max(nraw, 0), S);
+  const int P = max(praw, 0);
   if (tid == 0) {
     s_first = N;
     s_snap = 0;
@@ -48,15 +68,29 @@ __global__ __launch_bounds__(kScanThreads) void boundary_kernel(
   }
   __syncthreads();
 
-  // mask + first unstable position
+  // mask + first unstable position + delimiter ballots
   int first = N;
-  for (int base = 0; base < S; base += kScanThreads) {
+  for (int base = 0, k = 0; base < S; base += kScanThreads, ++k) {
     const int i = base + tid;
     const bool in = i < N;
-    const bool stable = in && mg[i] > tau;
+    float x;
+    int32_t v;
+    if (k < kKeep) {
+      x = mgr[k < kKeep ? k : 0];
+      v = idr[k < kKeep ? k : 0];
+    } else {
+      x = i < S ? mg[i] : 0.f;
+      v = i < S ? id[i] : 0;
+    }
+    const bool stable = in && x > tau;
     if (i < S) mk[i] = stable ? 1 : 0;
     const unsigned long long bal = __ballot(in && !stable);
     if (bal != 0ull && first == N) first = i - lane + __builtin_ctzll(bal);
+    if (snap_enabled) {
+      const bool d = in && unsigned(v) < unsigned(V) && ((bitmap[v >> 5] >> (v & 31)) & 1u);
+      const unsigned long long dbal = __ballot(d);
+      if (lane == 0) s_delim[(base + tid) >> 6] = dbal;
+    }
   }
   if (lane == 0 && first < N) atomicMin(&s_first, first);
   __syncthreads();
@@ -116,19 +150,16 @@ __global__ __launch_bounds__(kScanThreads) void boundary_kernel(
     }
   }
 
-  // last delimiter inside the window: candidate lengths j = Lp, Lp-1, ...
+  // last delimiter inside the window: candidate lengths j = lo .. Lp are positions
+  // lo-1 .. Lp-1 of the ballot words; one thread per word, highest set bit wins
   if (snap_enabled && Lp > 0) {
     const int lo = window < 0 ? 1 : max(1, Lp - window);
-    int best = 0;
-    for (int j = Lp - tid; j >= lo; j -= kScanThreads) {
-      const int32_t v = id[j - 1];
-      const bool d = unsigned(v) < unsigned(V) && ((bitmap[v >> 5] >> (v & 31)) & 1u);
-      if (d) {
-        best = j;
-        break;  // a lane's candidates only get shorter from here
-      }
+    const int w0 = (lo - 1) >> 6, w1 = (Lp - 1) >> 6;
+    for (int w = w0 + tid; w <= w1; w += kScanThreads) {
+      const int lowbit = max(lo - 1, 64 * w) - 64 * w, highbit = min(Lp - 1, 64 * w + 63) - 64 * w;
+      const unsigned long long m = s_delim[w] & (~0ull << lowbit) & (~0ull >> (63 - highbit));
+      if (m != 0ull) atomicMax(&s_snap, 64 * w + 64 - __builtin_clzll(m));
     }
-    if (best > 0) atomicMax(&s_snap, best);
   }
   __syncthreads();
   const int Ls = s_snap > 0 ? s_snap : Lp;
@@ -142,8 +173,14 @@ __global__ __launch_bounds__(kScanThreads) void boundary_kernel(
     L = max(T - P, 0);
     flag |= LSP_FLAG_TOKENS_FULL;
   }
-  if (tokens != nullptr)
-    for (int i = tid; i < L; i += kScanThreads) tokens[int64_t(b) * T + P + i] = id[i];
+  if (tokens != nullptr) {
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) {
+      const int i = k * kScanThreads + tid;
+      if (i < L) tokens[int64_t(b) * T + P + i] = idr[k];
+    }
+    for (int i = kKeep * kScanThreads + tid; i < L; i += kScanThreads) tokens[int64_t(b) * T + P + i] = id[i];
+  }
   if (tid == 0) {
     raw_boundary[b] = Lp;
     snapped_boundary[b] = Ls;
@@ -219,7 +256,7 @@ extern "C" int32_t lsp_commit(const lsp_commit_desc *d, const float *margin, con
                     snapped_boundary && commit_len,
                 "lsp_commit: null pointer");
   LSP_CHECK_ARG(d->B > 0 && d->S > 0 && d->V >= 2 && d->C > 0, "lsp_commit: bad B/S/V/C");
-  LSP_CHECK_ARG(d->B <= 65535, "lsp_commit: B must be <= 65535");
+  LSP_CHECK_ARG(d->B <= 65535 && d->S <= kMaxScanRows, "lsp_commit: B must be <= 65535 and S <= 65536");
   LSP_CHECK_ARG(d->min_commit >= 0, "lsp_commit: min_commit must be >= 0");
   LSP_CHECK_ARG(d->tau == d->tau, "lsp_commit: tau is NaN");
   LSP_CHECK_ARG(!d->snap_enabled || delimiter_bitmap, "lsp_commit: snapping needs a delimiter bitmap");
