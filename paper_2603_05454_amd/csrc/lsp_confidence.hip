@@ -31,6 +31,9 @@
 #include <type_traits>
 
 #include "lsp_common.h"
+#ifdef LSP_TUNE
+#include <stdlib.h>
+#endif
 
 namespace lsp {
 namespace {
@@ -371,6 +374,9 @@ inline Plan plan(int64_t rows, int V) {
   Plan p;
   int nt = 64;
   while (nt < 512 && rows * (nt / 64) < 2048) nt *= 2;
+#ifdef LSP_TUNE
+  if (getenv("LSP_CONF_NT")) nt = atoi(getenv("LSP_CONF_NT"));
+#endif
   int splits = 1;
   const int64_t waves = rows * (nt / 64);
   if (waves < 1024) {
