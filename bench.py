@@ -170,15 +170,28 @@ def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True, overl
     committed = int(sum(int(commit_out[i]["commit_len"].sum().item()) for i in range(Wm, Wm + K)))
     value = committed / wall
 
-    # ---- per-call timing (HIP events on the launch stream, back to back) ----------
+    # ---- per-call timing (HIP events on the launch stream, calls back to back) ------
+    # Launched the way the timed step is: replayed from a captured graph of `reps` calls when the
+    # step runs from a graph (eager launches of microsecond kernels would mostly time the host).
     def time_call(fn, reps):
         for i in range(3):
             fn(i)
         torch.cuda.synchronize()
+        g = None
+        if graph is not None:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for i in range(reps):
+                    fn(i)
+            g.replay()
+            torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
-        for i in range(reps):
-            fn(i)
+        if g is not None:
+            g.replay()
+        else:
+            for i in range(reps):
+                fn(i)
         b.record()
         torch.cuda.synchronize()
         return a.elapsed_time(b) * 1e-3 / reps

@@ -100,16 +100,21 @@ struct Geo {
 // addresses row (s/4), columns 4*(s%4)..+3 and receives column s of the 4 rows.
 // Contraction slot 8*hf+e of step k2 is key 16*k2 + 8*(e/4) + 4*hf + e%4 (the
 // accumulator row order of the first product).
-template <int D>
+// SWZ selects the tile layout: false = rows of pitch Geo<D>::VPITCH (padded);
+// true = unpadded rows of D*2 bytes whose 64-byte chunk c sits at chunk position
+// c ^ (row & 3), which is what loads that go from global memory straight into
+// LDS produce (they cannot pad, so they permute).
+template <int D, bool SWZ = false>
 __device__ __forceinline__ void load_v_frags(bf16x8 (&vf)[D / 32][2], int lane, const unsigned char *vtile) {
-  constexpr int VPITCH = Geo<D>::VPITCH;
+  constexpr int VPITCH = SWZ ? D * 2 : Geo<D>::VPITCH;
   const int hf = lane >> 5, s16 = lane & 15;
   const unsigned char *vbase = vtile + (4 * hf + (s16 >> 2)) * VPITCH + (16 * ((lane >> 4) & 1) + 4 * (s16 & 3)) * 2;
+  const int r3 = (s16 >> 2) & 3;  // row & 3 of every row this lane addresses
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
     for (int k2 = 0; k2 < 2; ++k2) {
-      const unsigned char *ap = vbase + (16 * k2) * VPITCH + 64 * db;
+      const unsigned char *ap = vbase + (16 * k2) * VPITCH + 64 * (SWZ ? (db ^ r3) : db);
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
           (__attribute__((address_space(3))) s16x4 *)(ap));
       const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -291,6 +296,16 @@ __device__ __forceinline__ void merge_store(const AttnArgs &a, const f32x16 (&oa
   }
 }
 
+// One wave-wide load from global memory straight into LDS: lane l fetches 16
+// bytes at its own address g and they land at lds_base + 16 l (lds_base is
+// wave-uniform; the counter to wait on is vmcnt, and loads complete in order).
+__device__ __forceinline__ void load_to_lds(const char *g, unsigned char *lds_base) {
+  __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void *)lds_base, 16, 0, 0);
+}
+constexpr int kWaitVm0 = 0x0F70;      // s_waitcnt vmcnt(0), other counters untouched
+constexpr int kWaitVm8 = 0x0F78;      // s_waitcnt vmcnt(8)
+constexpr int kWaitLgkm0 = 0xC07F;    // s_waitcnt lgkmcnt(0), other counters untouched
+
 // Body of the wave-private kernel for the WM*32 queries from q0 of (sequence b,
 // query head h, KV head g); every thread of a workgroup of 64*WM*WK threads
 // calls it with the same arguments (it contains barriers).
@@ -372,7 +387,45 @@ __device__ __forceinline__ void key_split_body(const AttnArgs &a, int b, int g, 
     softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, vf);
   };
 
-  if (wk < NB) load_kv(wk);
+  // (machinery of the head_dim-128 path, described where it is used below)
+  unsigned char *wl = smem + __builtin_amdgcn_readfirstlane(wave) * G::WAVE_LDS;  // scalar base for the loads
+  constexpr int KB = 32 * D * 2;                    // K rows, then V rows
+  const int pp = lane & 15, lr = lane >> 4;         // 16-byte position and row (of 4) inside a wave-wide load
+  int kcol[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) kcol[q] = 16 * (pp ^ ((4 * q + lr) & 15));
+  const int vswz = 64 * ((pp >> 2) ^ (lr & 3)) + 16 * (pp & 3);
+  const char *kcb = reinterpret_cast<const char *>(kc), *vcb = reinterpret_cast<const char *>(vc);
+  const char *ksb = reinterpret_cast<const char *>(ks), *vsb = reinterpret_cast<const char *>(vs);
+  const int64_t cpitch = a.cs[1] * 2, spitch = a.ks[1] * 2;
+  const int32_t *crows = GATHER ? a.cache_rows + int64_t(b) * a.C : nullptr;
+  const int Cmax = a.C - 1;
+  int64_t roff[8];  // byte offset of this lane's row of wave-wide load i, from the cache or the suffix base
+  auto issue_k = [=, &roff](int jb) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int t = min(32 * jb + 4 * i + lr, T - 1);
+      int crow = t;
+      if (GATHER && t < P) crow = min(max(crows[t], 0), Cmax);  // a bad index must not leave the buffer
+      roff[i] = t < P ? int64_t(crow) * cpitch : int64_t(t - P) * spitch;
+      load_to_lds((t < P ? kcb : ksb) + roff[i] + kcol[i & 3], wl + 1024 * i);
+    }
+  };
+  auto issue_v = [=, &roff](int jb) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int t = min(32 * jb + 4 * i + lr, T - 1);
+      load_to_lds((t < P ? vcb : vsb) + roff[i] + vswz, wl + KB + 1024 * i);
+    }
+  };
+  if constexpr (D == 128) {
+    if (wk < NB) {
+      issue_k(wk);
+      issue_v(wk);
+    }
+  } else {
+    if (wk < NB) load_kv(wk);
+  }
   // (the first K/V block is already on its way)
   // Q fragments (B operand of S^T = K.Q^T): query lq of this wave, d = 16*kk + 8*hf + 0..7.
   // The WK waves of a query block need the same 32 rows: the workgroup fetches
@@ -395,7 +448,50 @@ __device__ __forceinline__ void key_split_body(const AttnArgs &a, int b, int g, 
   for (int kk = 0; kk < KK; ++kk)
     qf[kk] = *reinterpret_cast<const bf16x8 *>(smem + WM * WK * G::WAVE_LDS + (wm * 32 + lq) * G::KPITCH + (16 * kk + 8 * hf) * 2);
 
-  for (int jb = wk; jb < NB; jb += WK) block(jb);
+  if constexpr (D == 128) {
+    // head_dim 128: K and V rows go from global memory straight into this wave's
+    // LDS region (no staging registers, no LDS store instructions on the critical
+    // path: at these sizes the eight waves' staging traffic, 128 KB written per
+    // block step, was a good part of a block's time).  A wave-wide load fills 1 KB
+    // = 4 unpadded rows of 256 bytes; bank conflicts are avoided by a swizzle that
+    // the loading lane applies to its GLOBAL address: K keeps 16-byte chunk c of
+    // row r at chunk position c ^ (r & 15), V keeps 64-byte chunk c at c ^ (r & 3).
+    // One region per wave: the K rows of the wave's next block are requested as
+    // soon as this block's K fragments sit in registers, its V rows as soon as
+    // the V^T fragments do.
+    const int y16 = 16 * (hf ^ (lq & 15));
+    int jb = wk;
+    // (the first block was requested before the Q rows, see above)
+    for (; jb < NB; jb += WK) {
+      const bool more = jb + WK < NB;
+      __builtin_amdgcn_s_waitcnt(kWaitVm8);  // all but the newest 8 loads (this block's V rows) have landed: K is there
+      bf16x8 kf[KK];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[kk] = *reinterpret_cast<const bf16x8 *>(wlds + lq * (D * 2) + ((32 * kk) ^ y16));
+      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);  // fragments are in registers: the K rows may be overwritten
+      if (more) issue_k(jb + WK);
+      f32x16 s;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
+      if (more) __builtin_amdgcn_s_waitcnt(kWaitVm8);  // V rows of this block (the next block's 8 K loads are newer)
+      else __builtin_amdgcn_s_waitcnt(kWaitVm0);
+      if (32 * jb + 32 > T) {  // keys beyond T contribute exact zeros: their owners overwrite the V slots
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (32 * jb + 4 * i + lr >= T) *reinterpret_cast<u32x4 *>(wlds + KB + 1024 * i + 16 * lane) = u32x4{0, 0, 0, 0};
+      }
+      bf16x8 vf[DB][2];
+      load_v_frags<D, true>(vf, lane, wlds + KB);
+      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+      if (more) issue_v(jb + WK);
+      softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, vf);
+    }
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);  // nothing of this wave is still on its way into LDS
+  } else {
+    for (int jb = wk; jb < NB; jb += WK) block(jb);
+  }
   merge_store<D, WM, WK>(a, oacc, mref, lsum, smem, b, h, q0, N);
 }
 
