@@ -28,6 +28,8 @@
 //    same query block (merged through LDS at the end).  Every wave streams its
 //    own K/V blocks and never waits for another wave, so a step with few
 //    active rows still fills 256 compute units and runs at memory latency.
+//    With head_dim 128 its K/V rows go from global memory straight into the
+//    wave's LDS region (global_load_lds_dwordx4, rows unpadded and swizzled).
 //  * attn_bf16_tile_kernel (long suffixes): the WM waves of a workgroup share
 //    each K/V block through a two-stage LDS ring (every wave fetches 1/WM of
 //    the block), one barrier per block; L1/L2 traffic per flop drops WM-fold,
