@@ -61,6 +61,38 @@ def test_single_key_and_tile_edges(lsp, oracle, dtype):
     _check_full(lsp, oracle, w, pl, sl)
 
 
+@pytest.mark.parametrize("dtype,B,Hq,S", [("f32", 2, 2, 150), ("bf16", 2, 2, 150), ("bf16", 8, 16, 320)])
+def test_large_scores_and_moving_maximum(lsp, oracle, dtype, B, Hq, S):
+    """Scores spanning hundreds of units whose maximum keeps rising along the key
+    axis (the soft-max reference has to move again and again), rows where a single
+    key takes all the weight, and rows whose large scores are all negative; at the
+    short-suffix and at the long-suffix launch shape (one sequence there is short
+    enough for the key-split mode)."""
+    w = W.scaled(W.C2, dtype=dtype, B=B, S=S, P=200, C=256, Hq=Hq, Hkv=2, D=128, seed=91)
+    pl = torch.full((B,), 200, dtype=torch.int32)
+    sl = torch.full((B,), S, dtype=torch.int32)
+    sl[-1] = 40
+    kv = W.make_layer_kv(w, 0, prefix_len=pl)
+    dt = kv["q"].dtype
+    ramp = torch.linspace(0.2, 6.0, 200).view(1, 200, 1, 1)
+    kv["k_cache"][:, :200] = (kv["k_cache"][:, :200].float() * ramp).to(dt)     # later keys score higher
+    kv["k_suf"] = (kv["k_suf"].float() * 6.0).to(dt)
+    kv["q"] = (kv["q"].float() * 3.0).to(dt)
+    kv["q"][0, 5] = (-kv["k_suf"][0, 7, :1].float() * 2.0).expand(Hq, -1).to(dt)  # all large scores negative but one direction
+    kv["q"][0, 6] = (kv["k_cache"][0, 150, :1].float() * 4.0).expand(Hq, -1).to(dt)  # one key takes everything
+    got = _run(lsp, kv, pl, sl)
+    rows = torch.tensor([[b, i, h] for b in range(B) for i in range(int(sl[b])) for h in (0, Hq - 1)
+                         if i < 8 or i % 37 == 0 or i >= int(sl[b]) - 2], dtype=torch.int32)
+    ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl, rows=rows)
+    sel = got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()]
+    assert not torch.isnan(sel).any()
+    # fp32: a score of magnitude ~300 summed over 128 products in fp32 is off by ~1e-5 of
+    # itself, and that absolute error is the relative error of its exponential: 1e-4, not the
+    # 1e-5 that holds for unit-scale scores.  bf16: the usual bound.
+    err = (sel - ref).abs().max().item()
+    assert err <= (1e-4 if dtype == "f32" else TOL[dtype]), err
+
+
 def test_explicit_scale(lsp, oracle):
     w = W.scaled(W.C2, B=1, S=64, P=64, C=64, Hq=2, Hkv=1, D=128, seed=5)
     pl, sl = W.make_lengths(w)
