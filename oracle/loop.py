@@ -11,17 +11,19 @@ from __future__ import annotations
 
 import torch
 
-from . import commit, confidence
+from . import commit, confidence, lm_head_confidence
 
 
 def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
                 prefix_len, suffix_len, tokens, kv_layers=None, max_steps=100000, trace=False,
-                commit_kw=None):
+                commit_kw=None, lm_head_weight=None):
     """logits_fn(step, prefix_len) -> [B,S,V] CPU tensor (row u = u-th active position).
     prefix_len / suffix_len / tokens / kv_layers (list of dicts with k_suf,
     v_suf [B,S,Hkv,D], row u = u-th active position, reused unchanged by every
     step, and k_cache, v_cache) are updated in place.
     commit_kw: extra keyword arguments of oracle.commit (adaptive, alpha, beta, max_commit).
+    lm_head_weight [V,K]: logits_fn then returns the step's HIDDEN states [B,S,K] and
+    the logits are hidden @ weight.T kept in double (Algorithm 1 lines 4-5 together).
     Returns dict(steps, flips, flip_denominator, committed, per_step=[...])."""
     B = prefix_len.shape[0]
     P0 = prefix_len.clone()
@@ -32,7 +34,10 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     while int(suffix_len.max()) > 0:
         assert steps < max_steps
         z = logits_fn(steps, prefix_len)
-        ids, prob, mar = confidence(z, suffix_len)
+        if lm_head_weight is None:
+            ids, prob, mar = confidence(z, suffix_len)
+        else:
+            ids, prob, mar = lm_head_confidence(z, lm_head_weight, suffix_len)
         done = (prefix_len - P0).long()
         for b in range(B):
             n = int(suffix_len[b])

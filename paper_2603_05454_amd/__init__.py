@@ -171,6 +171,10 @@ def confidence(logits, suffix_len=None, out=None, workspace=None):
     return out
 
 
+def lm_head_confidence_workspace_bytes(B, S, V) -> int:
+    return lib().lsp_lm_head_confidence_workspace_bytes(B, S, V)
+
+
 def lm_head_confidence(hidden, weight, suffix_len=None, out=None, workspace=None):
     """lsp_lm_head_confidence: hidden [B,S,K], weight [V,K] (bf16) ->
     (top1_id int32, top1_prob f32, margin f32), [B,S], of the logits hidden @ weight.T,

@@ -10,13 +10,14 @@ from __future__ import annotations
 
 import torch
 
-from . import LayerTable, attn_step, commit, confidence, flip_update
+from . import (LayerTable, attn_step, commit, confidence, flip_update, lm_head_confidence,
+               lm_head_confidence_workspace_bytes)
 
 
 def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
                 prefix_len, suffix_len, tokens, kv_layers=None, gen_len=None, run_attention=False,
                 poll=1, max_steps=100000, stop_after=None, observer=None, timed=False, commit_kw=None,
-                graph=False):
+                graph=False, lm_head_weight=None):
     """logits_fn(step, prefix_len) -> device logits [B,S,V].  prefix_len,
     suffix_len, tokens and the caches in kv_layers (list of dicts q?, k_suf,
     v_suf, k_cache, v_cache) are updated in place.
@@ -26,6 +27,9 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     (the tensors are reused by the next step: copy what is to be kept).
     timed: bracket every step's library calls with HIP events on the current
     stream and return their sum as lsp_ms (the logits callback is outside).
+    lm_head_weight [V,K] (bf16): logits_fn then returns the step's HIDDEN states
+    [B,S,K] and lsp_lm_head_confidence takes the place of lsp_confidence (the
+    logits are never stored).
     graph: launch every step after the first from ONE captured HIP graph (all
     sequence state lives in device memory and no entry point reads it on the
     host, so the same graph serves every step); the first step runs eagerly.
@@ -47,14 +51,20 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     attn_out = None
     events = []
     zbuf = step_graph = None
+    lm_ws = None   # workspace of the fused output head: allocated by the first (eager) step, then reused
 
     def one_step(z):
-        nonlocal out, conf, attn_out
+        nonlocal out, conf, attn_out, lm_ws
         if run_attention and kv_layers is not None:
             for L in kv_layers:
                 attn_out = attn_step(L["q"], L["k_suf"], L["v_suf"], L["k_cache"], L["v_cache"],
                                      prefix_len, suffix_len, out=attn_out)
-        conf = confidence(z, suffix_len, out=conf)
+        if lm_head_weight is None:
+            conf = confidence(z, suffix_len, out=conf)
+        else:
+            if lm_ws is None:
+                lm_ws = torch.empty(lm_head_confidence_workspace_bytes(z.shape[0], z.shape[1], V), dtype=torch.uint8, device=dev)
+            conf = lm_head_confidence(z, lm_head_weight, suffix_len, out=conf, workspace=lm_ws)
         flip_update(conf[0], prefix_len, suffix_len, base, last_id, counters)
         out = commit(conf[2], conf[0], bitmap, V, tau, window, min_commit, snap_enabled,
                      prefix_len, suffix_len, tokens=tokens, layers=table, C=tokens.shape[1], out=out,

@@ -49,6 +49,37 @@ def test_small_loop_matches_oracle(lsp, oracle, tau, Lmin, sizing, graph):
         assert torch.equal(Lg["v_cache"].cpu().view(torch.int16), Lr["v_cache"].view(torch.int16))
 
 
+@pytest.mark.parametrize("graph", [False, True])
+def test_loop_driven_by_the_fused_output_head(lsp, oracle, graph):
+    """The loop with lsp_lm_head_confidence in the place of lsp_confidence: the
+    step's input is a hidden state, the logits are never stored.  Small-integer
+    operands make every logit exact in fp32, so the whole loop - ids, margins,
+    boundaries, tokens, steps, flips - must match the oracle loop bit for bit
+    (tied maxima, margin 0, occur in nearly every step)."""
+    from paper_2603_05454_amd.loop import decode_loop as gpu_loop
+    G, K = 80, 64
+    w = W.scaled(W.C5, B=3, S=G, V=1000, P=8, gen_len=G, C=8 + G, layers=1, Hq=2, Hkv=2, D=64)
+    _, bm = W.make_delimiters(w)
+    gw = torch.Generator().manual_seed(5)
+    weight = torch.randint(-3, 4, (w.V, K), generator=gw).to(torch.bfloat16)
+
+    def hidden_fn(step, p):
+        g = torch.Generator().manual_seed(100 + step)
+        return torch.randint(-3, 4, (w.B, w.S, K), generator=g).to(torch.bfloat16)
+
+    pl, sl = W.make_lengths(w)
+    tokens = W.make_tokens(w, w.C)
+    ref = decode_loop(hidden_fn, bm, w.V, 0.5, w.window, 1, 1, pl, sl, tokens, lm_head_weight=weight)
+    pl_g, sl_g = (t.cuda() for t in W.make_lengths(w))
+    tok_g = W.make_tokens(w, w.C).cuda()
+    got = gpu_loop(lambda s, p: hidden_fn(s, p).cuda(), bm.cuda(), w.V, 0.5, w.window, 1, 1, pl_g, sl_g, tok_g,
+                   gen_len=G, lm_head_weight=weight.cuda(), graph=graph)
+    assert (got["steps"], got["flips"], got["flip_denominator"], got["committed"]) == \
+           (ref["steps"], ref["flips"], ref["flip_denominator"], ref["committed"])
+    assert ref["steps"] > 3
+    assert torch.equal(tok_g.cpu(), tokens) and torch.equal(pl_g.cpu(), pl) and torch.equal(sl_g.cpu(), sl)
+
+
 def test_c5_full_size_first_steps_sampled(lsp, oracle):
     """Config 5 at its full shape (batch 16, 32 layers, 1024 active rows, vocab
     126464), first steps of the loop in the launch configuration bench.py uses.

@@ -87,3 +87,29 @@ def test_restart_from_snapshot(oracle):
     rest = decode_loop(lambda s, p: fn(s + 3, p), bm, w.V, w.tau, w.window, 1, 1, pl2, sl2, tok2)
     assert rest["steps"] + 3 == full["steps"]
     assert torch.equal(tok2, tokens)
+
+
+def test_loop_on_hidden_states_equals_loop_on_their_logits(oracle):
+    """lm_head_weight mode: with operands whose logits are exact in fp32 the loop
+    fed hidden states must walk exactly like the loop fed the logits themselves."""
+    import workloads as W
+    from oracle.loop import decode_loop
+    G, K = 40, 16
+    w = W.scaled(W.C5, B=2, S=G, V=300, P=4, gen_len=G, C=4 + G, layers=1, Hq=2, Hkv=2, D=64)
+    _, bm = W.make_delimiters(w)
+    weight = torch.randint(-3, 4, (w.V, K), generator=torch.Generator().manual_seed(1)).float()
+
+    def hidden_fn(step, p):
+        return torch.randint(-3, 4, (w.B, w.S, K), generator=torch.Generator().manual_seed(50 + step)).float()
+
+    runs = []
+    for mode in ("hidden", "logits"):
+        pl, sl = W.make_lengths(w)
+        tokens = W.make_tokens(w, w.C)
+        if mode == "hidden":
+            r = decode_loop(hidden_fn, bm, w.V, 0.5, w.window, 1, 1, pl, sl, tokens, lm_head_weight=weight)
+        else:
+            r = decode_loop(lambda s, p: hidden_fn(s, p) @ weight.T, bm, w.V, 0.5, w.window, 1, 1, pl, sl, tokens)
+        runs.append((r["steps"], r["flips"], r["flip_denominator"], r["committed"], tokens.clone(), pl.clone()))
+    assert runs[0][:4] == runs[1][:4] and runs[0][0] > 2
+    assert torch.equal(runs[0][4], runs[1][4]) and torch.equal(runs[0][5], runs[1][5])
