@@ -106,6 +106,21 @@ struct Geo {
 // true = unpadded rows of D*2 bytes whose 64-byte chunk c sits at chunk position
 // c ^ (row & 3), which is what loads that go from global memory straight into
 // LDS produce (they cannot pad, so they permute).
+// One V^T fragment: two transpose loads, rows r..r+3 and r+8..r+11 of a tile with
+// PITCH bytes per row, at the address of this lane's piece of row r.
+// The pointer is declared restrict for the sake of the compiler's wait-count
+// tracking: without alias scope information every transpose load is made to
+// wait for ALL outstanding global -> LDS loads (vmcnt(0)), also those that fill
+// other rows; the waits that order these reads after the loads they do depend
+// on are written out where the kernels issue such loads.
+template <int PITCH>
+__device__ __forceinline__ bf16x8 vt_read(const unsigned char *__restrict__ ap) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(ap));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(ap + 8 * PITCH));
+  const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+  const u32x4 w = {l2.x, l2.y, h2.x, h2.y};
+  return __builtin_bit_cast(bf16x8, w);
+}
 template <int D, bool SWZ = false>
 __device__ __forceinline__ void load_v_frags(bf16x8 (&vf)[D / 32][2], int lane, const unsigned char *vtile) {
   constexpr int VPITCH = SWZ ? D * 2 : Geo<D>::VPITCH;
@@ -115,16 +130,8 @@ __device__ __forceinline__ void load_v_frags(bf16x8 (&vf)[D / 32][2], int lane, 
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-    for (int k2 = 0; k2 < 2; ++k2) {
-      const unsigned char *ap = vbase + (16 * k2) * VPITCH + 64 * (SWZ ? (db ^ r3) : db);
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4 *)(ap));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4 *)(ap + 8 * VPITCH));
-      const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-      const u32x4 w = {l2.x, l2.y, h2.x, h2.y};
-      vf[db][k2] = __builtin_bit_cast(bf16x8, w);
-    }
+    for (int k2 = 0; k2 < 2; ++k2)
+      vf[db][k2] = vt_read<VPITCH>(vbase + (16 * k2) * VPITCH + 64 * (SWZ ? (db ^ r3) : db));
 }
 
 // Second half of a 32-key block, shared by both kernels: soft-max of the score
@@ -403,7 +410,31 @@ __device__ __forceinline__ void key_split_body(const AttnArgs &a, int b, int g, 
   const int32_t *crows = GATHER ? a.cache_rows + int64_t(b) * a.C : nullptr;
   const int Cmax = a.C - 1;
   int64_t roff[8];  // byte offset of this lane's row of wave-wide load i, from the cache or the suffix base
+  // A block that lies wholly in the cache or wholly in the suffix (all but one or
+  // two of a wave's blocks) is a wave-uniform base, stepped by four rows per load
+  // on the scalar unit, plus a 32-bit lane offset computed once; the general form
+  // costs about ten vector instructions per load.
+  uint32_t kofc[4], kofs[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    kofc[q] = uint32_t(lr * cpitch + kcol[q]);
+    kofs[q] = uint32_t(lr * spitch + kcol[q]);
+  }
+  const uint32_t vofc = uint32_t(lr * cpitch + vswz), vofs = uint32_t(lr * spitch + vswz);
   auto issue_k = [=, &roff](int jb) __attribute__((always_inline)) {
+    const int t0 = 32 * jb;
+    if (!GATHER && t0 + 32 <= P) {
+      const char *base = kcb + int64_t(t0) * cpitch;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) load_to_lds(base + int64_t(4 * i) * cpitch + kofc[i & 3], wl + 1024 * i);
+      return;
+    }
+    if (t0 >= P && t0 + 32 <= T) {
+      const char *base = ksb + int64_t(t0 - P) * spitch;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) load_to_lds(base + int64_t(4 * i) * spitch + kofs[i & 3], wl + 1024 * i);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int t = min(32 * jb + 4 * i + lr, T - 1);
@@ -414,16 +445,30 @@ __device__ __forceinline__ void key_split_body(const AttnArgs &a, int b, int g, 
     }
   };
   auto issue_v = [=, &roff](int jb) __attribute__((always_inline)) {
+    const int t0 = 32 * jb;
+    if (!GATHER && t0 + 32 <= P) {
+      const char *base = vcb + int64_t(t0) * cpitch;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) load_to_lds(base + int64_t(4 * i) * cpitch + vofc, wl + KB + 1024 * i);
+      return;
+    }
+    if (t0 >= P && t0 + 32 <= T) {
+      const char *base = vsb + int64_t(t0 - P) * spitch;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) load_to_lds(base + int64_t(4 * i) * spitch + vofs, wl + KB + 1024 * i);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int t = min(32 * jb + 4 * i + lr, T - 1);
       load_to_lds((t < P ? vcb : vsb) + roff[i] + vswz, wl + KB + 1024 * i);
     }
   };
+  const int wk_s = __builtin_amdgcn_readfirstlane(wk);  // the same value, known to be wave-uniform
   if constexpr (D == 128) {
-    if (wk < NB) {
-      issue_k(wk);
-      issue_v(wk);
+    if (wk_s < NB) {
+      issue_k(wk_s);
+      issue_v(wk_s);
     }
   } else {
     if (wk < NB) load_kv(wk);
@@ -462,7 +507,7 @@ __device__ __forceinline__ void key_split_body(const AttnArgs &a, int b, int g, 
     // soon as this block's K fragments sit in registers, its V rows as soon as
     // the V^T fragments do.
     const int y16 = 16 * (hf ^ (lq & 15));
-    int jb = wk;
+    int jb = wk_s;
     // (the first block was requested before the Q rows, see above)
     for (; jb < NB; jb += WK) {
       const bool more = jb + WK < NB;
