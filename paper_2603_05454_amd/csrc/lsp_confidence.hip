@@ -234,7 +234,12 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
   };
   // phase 1: top-2 over the whole group, one index tag and one reference check per
   // group; phase 2: the soft-max sum.  (The tag names the lane's first vector of the
-  // group; the lane's U vectors of that group are re-read at the end.)
+  // group; the lane keeps a copy of its U vectors of that group, eight selects per
+  // group, and scans the copy at the end.  Re-reading them from memory instead put
+  // a dependent round trip at the end of every row.)
+  u32x4 kept[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) kept[u] = u32x4{0, 0, 0, 0};
   auto process_group = [&](const u32x4 (&buf)[U], int g, auto last) {
     float x[U][N];
     const float old = t.m1;
@@ -247,7 +252,15 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
       }
       absorb_top2<N>(t, x[u]);
     }
-    t.idx = t.m1 > old ? ~(vbase + (g * G + tid) * N) : t.idx;
+    const bool rose = t.m1 > old;
+    t.idx = rose ? ~(vbase + (g * G + tid) * N) : t.idx;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      kept[u].x = rose ? buf[u].x : kept[u].x;
+      kept[u].y = rose ? buf[u].y : kept[u].y;
+      kept[u].z = rose ? buf[u].z : kept[u].z;
+      kept[u].w = rose ? buf[u].w : kept[u].w;
+    }
     settle_reference(t);
 #pragma unroll
     for (int u = 0; u < U; ++u) absorb_sum<N>(t, x[u]);
@@ -284,20 +297,18 @@ __global__ __launch_bounds__(NT) void confidence_kernel(
     absorb<1>(t, x, tail0 + tid);
   }
 
-  // Only a lane that holds the wave's maximum can own the arg-max, so only such
-  // a lane (usually one) re-reads its remembered group: its U vectors of that
-  // group, scanned from the last to the first so that the lowest index wins.
+  // A lane whose maximum came from a group scans its copy of that group, from the
+  // last vector to the first so that the lowest index wins.
   const float wave_max = wave_reduce(t.m1, OpMax());
-  if (t.idx < 0 && t.m1 == wave_max) {
+  if (t.idx < 0) {
     const int e0 = ~t.idx;
     int found = INT_MAX;
 #pragma unroll
     for (int u = U - 1; u >= 0; --u) {
       const int eb = e0 + u * NT * N;
-      if (eb >= tail0) continue;  // past the end of a partial group
-      const u32x4 w = *reinterpret_cast<const u32x4 *>(row + eb);
+      if (eb >= tail0) continue;  // past the end of a partial group (the copy holds a repeat of the last vector)
       float x[N];
-      Vec<T>::unpack(w, x);
+      Vec<T>::unpack(kept[u], x);
 #pragma unroll
       for (int k = N - 1; k >= 0; --k) found = (x[k] == t.m1) ? eb + k : found;
     }
