@@ -34,6 +34,10 @@
 //    each K/V block through a two-stage LDS ring (every wave fetches 1/WM of
 //    the block), one barrier per block; L1/L2 traffic per flop drops WM-fold,
 //    which is what the matrix cores need once the problem is compute bound.
+// and, for head_dim 128 and suffix buffers of more than 128 rows, a third form of
+// the long-suffix kernel, attn_bf16_ring_kernel (eight waves, K/V straight from
+// global memory into an eight-stage LDS ring, one barrier every four blocks),
+// described where it is defined.
 #include "lsp_attn.h"
 #ifdef LSP_TUNE
 #include <stdlib.h>
@@ -600,21 +604,6 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
   const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
   const int N = min(max(a.suffix_len[b], 0), a.S);
   const int P = min(max(a.prefix_len[b], 0), a.C);
-  // A sequence whose suffix is down to a few rows (the late steps of a decode
-  // loop) would keep this wide tile busy for the whole key range with most of
-  // its queries masked.  Its first tiles then each take ONE block of 32 queries
-  // and split the KEY range between their waves instead.  Lengths live in device
-  // memory, so the choice is made here, per workgroup, not by the launcher.
-  // (Only the eight-wave form: it owns its compute unit anyway, so the larger LDS
-  // footprint of the key-split mode costs no occupancy.)
-  if constexpr (WM == 8) {
-    const int tile = q0 / (32 * WM), QT = (a.S + 32 * WM - 1) / (32 * WM);
-    const int short_rows = 32 * min(QT, kShortSuffix / 32);
-    if (N <= short_rows) {
-      if (32 * tile < N) key_split_body<D, 1, WM, GATHER>(a, b, g, h, 32 * tile, N, P, smem);
-      return;
-    }
-  }
   if (q0 >= N) return;
   const int T = P + N;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -767,10 +756,7 @@ int32_t launch_tile_g(AttnArgs a, hipStream_t st) {
     set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
     return LSP_ERR_UNSUPPORTED;
   }
-  // two shared stages, or the key-split mode's WM wave regions + 32 Q rows
-  const size_t lds_tile = 2 * size_t(TileGeo<D>::STAGE);
-  const size_t lds_split = WM == 8 ? size_t(WM) * Geo<D>::WAVE_LDS + 32 * size_t(Geo<D>::KPITCH) : 0;
-  const size_t lds = lds_tile > lds_split ? lds_tile : lds_split;
+  const size_t lds = 2 * size_t(TileGeo<D>::STAGE);  // two shared stages
   auto kern = attn_bf16_tile_kernel<D, WM, OCC, PD, GATHER>;
   static bool configured = false;  // per instantiation
   if (!configured) {
@@ -781,6 +767,243 @@ int32_t launch_tile_g(AttnArgs a, hipStream_t st) {
   }
   kern<<<dim3(static_cast<unsigned>(nwg), 1, 1), 64 * WM, lds, st>>>(a);
   LSP_CHECK_LAUNCH("lsp_attn_step: bf16 tile launch");
+  return LSP_OK;
+}
+
+// ---- long-suffix kernel, head_dim 128: K/V blocks go global -> LDS directly --------
+// Same arithmetic as attn_bf16_tile_kernel, different plumbing.  Every 32-key
+// block is fetched with two wave-wide global_load_lds_dwordx4 per wave (1 KB = 4
+// rows of K, 1 KB = 4 rows of V) into a ring of NS stages of 16 KB, NS-BS blocks
+// ahead of the products: the prefetch depth costs LDS instead of registers and
+// no LDS store instruction is issued.  Rows are unpadded and swizzled as in the
+// key-split body.  LDS holds the K tiles of all stages first, then the V tiles,
+// so that every fragment read is a per-lane address computed once plus an
+// immediate offset (the loop is unrolled NS times).
+// The workgroup synchronises once every BS blocks, not every block: before
+// that barrier a wave waits until its shares of the next BS blocks have landed;
+// between barriers the eight waves run free (up to BS blocks apart), so the two
+// waves of a SIMD drift out of phase and use the matrix and the vector pipeline
+// at different times.  Iteration j requests block j+NS-BS into the stage that
+// block j-BS was read from, which every wave left before the last barrier.
+// (Measured on config 4, NS = 8: 704 us for the tile kernel, 702 us with a
+// barrier per block, 685 us with one every two, 680 us with one every four.)
+struct RingLoad {
+  const char *kc, *vc, *ks, *vs;   // this (sequence, KV head)'s cache and suffix rows
+  int64_t cpitch, spitch;          // bytes between rows
+  uint32_t kc_off, vc_off, ks_off, vs_off;  // row-in-block * pitch + swizzled column (cache / suffix)
+  const int32_t *cache_rows;       // indexed cache: this sequence's row table, else null
+  int kcol, vcol, lr, P, T, C;
+};
+template <bool GATHER>
+__device__ __forceinline__ void ring_issue(RingLoad L, int jb, unsigned char *kdst, unsigned char *vdst) {
+  const int t0 = 32 * jb;
+  const char *kp, *vp;
+  if (!GATHER && t0 + 32 <= L.P) {            // block wholly in the cache: wave-uniform base + fixed lane offset
+    const int64_t base = int64_t(t0) * L.cpitch;
+    kp = L.kc + base + L.kc_off;
+    vp = L.vc + base + L.vc_off;
+  } else if (t0 >= L.P && t0 + 32 <= L.T) {   // wholly in the suffix
+    const int64_t base = int64_t(t0 - L.P) * L.spitch;
+    kp = L.ks + base + L.ks_off;
+    vp = L.vs + base + L.vs_off;
+  } else {                                    // straddles the boundary, ragged end, or indexed cache rows
+    const int t = min(t0 + L.lr, L.T - 1);
+    if (t < L.P) {
+      int crow = t;
+      if (GATHER) crow = min(max(L.cache_rows[t], 0), L.C - 1);  // a bad index must not leave the buffer
+      kp = L.kc + int64_t(crow) * L.cpitch + L.kcol;
+      vp = L.vc + int64_t(crow) * L.cpitch + L.vcol;
+    } else {
+      kp = L.ks + int64_t(t - L.P) * L.spitch + L.kcol;
+      vp = L.vs + int64_t(t - L.P) * L.spitch + L.vcol;
+    }
+  }
+  load_to_lds(kp, kdst);
+  load_to_lds(vp, vdst);
+}
+template <int NS, int BS, bool GATHER>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_ring_kernel(AttnArgs a) {
+  constexpr int D = 128, WM = 8, KK = D / 16, DB = D / 32;
+  constexpr int TILE = 32 * D * 2, VBASE = NS * TILE;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  const Place pl = place(a, 32 * WM);
+  if (!pl.valid) return;
+  const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
+  const int N = min(max(a.suffix_len[b], 0), a.S);
+  const int P = min(max(a.prefix_len[b], 0), a.C);
+  // A sequence whose suffix is down to a few rows (the late steps of a decode
+  // loop) would keep this wide tile busy for the whole key range with most of
+  // its queries masked.  Its first tiles then each take ONE block of 32 queries
+  // and split the KEY range between their waves instead.  Lengths live in device
+  // memory, so the choice is made here, per workgroup, not by the launcher.
+  // (This workgroup owns its compute unit anyway, so the larger LDS footprint of
+  // the key-split mode costs no occupancy.)
+  {
+    const int tile = q0 / (32 * WM), QT = (a.S + 32 * WM - 1) / (32 * WM);
+    const int short_rows = 32 * min(QT, kShortSuffix / 32);
+    if (N <= short_rows) {
+      if (32 * tile < N) key_split_body<D, 1, WM, GATHER>(a, b, g, h, 32 * tile, N, P, smem);
+      return;
+    }
+  }
+  if (q0 >= N) return;
+  const int T = P + N;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int lq = lane & 31, hf = lane >> 5;
+
+  const int qi = q0 + wave * 32 + lq;
+  const uint16_t *qp = static_cast<const uint16_t *>(a.q) + b * a.qs[0] + int64_t(min(qi, N - 1)) * a.qs[1] + h * a.qs[2];
+  bf16x8 qf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8 *>(qp + 16 * kk + 8 * hf);
+  asm volatile("" ::: "memory");  // the Q loads stay ahead of the requests below: the first wait then covers them
+
+  // loader: this lane owns row lr of every block and 16-byte position pp of it
+  RingLoad L;
+  L.kc = reinterpret_cast<const char *>(static_cast<const uint16_t *>(a.k_cache) + b * a.cs[0] + g * a.cs[2]);
+  L.vc = reinterpret_cast<const char *>(static_cast<const uint16_t *>(a.v_cache) + b * a.cs[0] + g * a.cs[2]);
+  L.ks = reinterpret_cast<const char *>(static_cast<const uint16_t *>(a.k_suf) + b * a.ks[0] + g * a.ks[2]);
+  L.vs = reinterpret_cast<const char *>(static_cast<const uint16_t *>(a.v_suf) + b * a.ks[0] + g * a.ks[2]);
+  L.cpitch = a.cs[1] * 2;
+  L.spitch = a.ks[1] * 2;
+  {
+    const int pp = lane & 15;
+    L.lr = 4 * wave + (lane >> 4);
+    L.kcol = 16 * (pp ^ (L.lr & 15));
+    L.vcol = 64 * ((pp >> 2) ^ (L.lr & 3)) + 16 * (pp & 3);
+    L.kc_off = uint32_t(L.lr * L.cpitch + L.kcol);
+    L.vc_off = uint32_t(L.lr * L.cpitch + L.vcol);
+    L.ks_off = uint32_t(L.lr * L.spitch + L.kcol);
+    L.vs_off = uint32_t(L.lr * L.spitch + L.vcol);
+  }
+  L.cache_rows = GATHER ? a.cache_rows + int64_t(b) * a.C : nullptr;
+  L.P = P;
+  L.T = T;
+  L.C = a.C;
+  const int NB = (T + 31) >> 5;
+  static_assert(NS % BS == 0 && NS >= 2 * BS, "ring depth and barrier period");
+  constexpr int kWaitRing = 0x0F70 | (2 * (NS - 2 * BS));  // s_waitcnt vmcnt: all but the newest NS-2BS blocks (two loads each) have landed
+#define LSP_RING_ISSUE(jb_, slot_) \
+  ring_issue<GATHER>(L, (jb_), smem + (slot_) * TILE + 1024 * wave_s, smem + VBASE + (slot_) * TILE + 1024 * wave_s)
+  // prologue: blocks 0 .. NS-BS-1 into their stages (block indices beyond the
+  // last one fetch the last block again, into a stage nobody reads, so that the
+  // number of loads in flight is the same everywhere)
+#pragma unroll
+  for (int u = 0; u < NS - BS; ++u) LSP_RING_ISSUE(min(u, NB - 1), u);
+
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float mref = -INFINITY, lsum = 0.f;
+  const float sc = a.scale * kLog2e;
+
+  // Fragment addresses, computed once.  K: row lq of a tile, 16-byte chunk
+  // 2*kk + hf at its swizzled position.  V^T: as in load_v_frags (SWZ form), one
+  // address per 32-wide d block; the k2 steps and fragment halves are offsets.
+  const unsigned char *kaddr[KK], *vaddr[DB];
+  {
+    const int y16 = 16 * (hf ^ (lq & 15));
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kaddr[kk] = smem + lq * (D * 2) + ((32 * kk) ^ y16);
+    const int s16 = lane & 15, r3 = (s16 >> 2) & 3;
+    const unsigned char *vbase = smem + VBASE + (4 * hf + (s16 >> 2)) * (D * 2) + (16 * ((lane >> 4) & 1) + 4 * (s16 & 3)) * 2;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) vaddr[db] = vbase + 64 * (db ^ r3);
+  }
+  // keys beyond T contribute exact zeros: once the block has landed, the lanes
+  // that own such rows overwrite their V slots (cold: the ragged last block only)
+  auto zero_beyond = [&](int jb, int slot) {
+    if (32 * jb + 32 <= T || jb >= NB) return;
+    if (32 * jb + L.lr >= T)
+      *reinterpret_cast<u32x4 *>(smem + VBASE + slot * TILE + 1024 * wave + 16 * lane) = u32x4{0, 0, 0, 0};
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+  };
+  auto sync = [&]() {  // plain barrier: newer loads stay in flight; no LDS access is moved across it
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+
+  __builtin_amdgcn_s_waitcnt(kWaitRing);  // blocks 0 .. BS-1 (and the Q rows) have arrived
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) asm volatile("" : "+v"(qf[kk]));  // (their wait is here, not in the loop)
+#pragma unroll
+  for (int k = 0; k < BS; ++k) zero_beyond(k, k);
+  sync();
+  for (int jb0 = 0; jb0 < NB; jb0 += NS) {
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+      const int jb = jb0 + u;
+      if (jb >= NB) break;
+      // the stage that block jb-BS was read from is free since the last barrier
+      LSP_RING_ISSUE(min(jb + NS - BS, NB - 1), (u + NS - BS) % NS);
+      bf16x8 kf[KK];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[kk] = *reinterpret_cast<const bf16x8 *>(kaddr[kk] + u * TILE);
+      f32x16 s;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
+      bf16x8 vf[DB][2];
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) vf[db][k2] = vt_read<D * 2>(vaddr[db] + u * TILE + (16 * k2) * (D * 2));
+      __builtin_amdgcn_sched_barrier(0);
+      softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, vf);
+      if ((u % BS) == BS - 1) {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(kWaitRing);  // blocks jb+1 .. jb+BS have landed
+#pragma unroll
+        for (int k = 1; k <= BS; ++k) zero_beyond(jb + k, (u + k) % NS);
+        sync();
+      }
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(kWaitVm0);  // nothing of this wave is still on its way into LDS
+#undef LSP_RING_ISSUE
+  lsum = half_sum(lsum);
+  if (qi < N) {
+    const float inv = 1.0f / lsum;
+    uint16_t *op = static_cast<uint16_t *>(a.out) + b * a.os[0] + int64_t(qi) * a.os[1] + h * a.os[2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        u32x2 w;
+        w.x = pack_bf16(oacc[db][4 * r4] * inv, oacc[db][4 * r4 + 1] * inv);
+        w.y = pack_bf16(oacc[db][4 * r4 + 2] * inv, oacc[db][4 * r4 + 3] * inv);
+        *reinterpret_cast<u32x2 *>(op + 32 * db + 8 * r4 + 4 * hf) = w;
+      }
+  }
+}
+
+template <int NS, int BS, bool GATHER>
+int32_t launch_ring_g(AttnArgs a, hipStream_t st) {
+  const int64_t nwg = place_grid(a, 256);
+  if (nwg > 0x7fffffff) {
+    set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
+    return LSP_ERR_UNSUPPORTED;
+  }
+  // the ring, or the key-split mode's eight wave regions + 32 Q rows
+  const size_t lds_ring = size_t(NS) * 2 * 32 * 256;
+  const size_t lds_split = 8 * size_t(Geo<128>::WAVE_LDS) + 32 * size_t(Geo<128>::KPITCH);
+  const size_t lds = lds_ring > lds_split ? lds_ring : lds_split;
+  auto kern = attn_bf16_ring_kernel<NS, BS, GATHER>;
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+    if (e != hipSuccess) return hip_fail(e, "lsp_attn_step: hipFuncSetAttribute");
+    configured = true;
+  }
+  kern<<<dim3(static_cast<unsigned>(nwg), 1, 1), 512, lds, st>>>(a);
+  LSP_CHECK_LAUNCH("lsp_attn_step: bf16 ring launch");
   return LSP_OK;
 }
 
@@ -802,7 +1025,7 @@ int32_t dispatch(const AttnArgs &a, hipStream_t st) {
   const int64_t rows = int64_t(a.B) * a.Hq * a.S;  // upper bound on (b,h,row) triples
   if (rows / 128 >= 256) {
     if constexpr (D == 128) {
-      if (a.S > 128) return launch_tile<D, 8, 2, 6>(a, st);
+      if (a.S > 128) return a.cache_rows ? launch_ring_g<8, 4, true>(a, st) : launch_ring_g<8, 4, false>(a, st);
     }
     return launch_tile<D, 4, 2, 4>(a, st);
   }

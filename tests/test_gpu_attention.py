@@ -190,9 +190,9 @@ def test_many_rows_ragged_lengths_sampled(lsp, oracle, D, Hq, Hkv, S):
 
 
 def test_mixed_short_and_long_suffixes_in_one_call(lsp, oracle):
-    """At the long-suffix launch shape the sequences whose suffix is down to a few
-    rows are served by a second launch (key range split between waves): lengths on
-    both sides of that split, in one call, every active row against the oracle."""
+    """At the long-suffix launch shape the workgroups of a sequence whose suffix is
+    down to a few rows switch to the key-split mode: lengths on both sides of that
+    switch, in one call, sampled active rows against the oracle."""
     w = W.scaled(W.C2, B=8, S=320, P=200, C=256, Hq=16, Hkv=4, D=128, seed=77)
     pl = torch.tensor([200, 256, 0, 31, 200, 97, 256, 5], dtype=torch.int32)
     sl = torch.tensor([0, 1, 33, 64, 65, 200, 320, 31], dtype=torch.int32)
@@ -203,6 +203,42 @@ def test_mixed_short_and_long_suffixes_in_one_call(lsp, oracle):
     ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl, rows=rows)
     sel = got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()]
     assert (sel - ref).abs().max().item() <= 2e-2
+    for b in range(w.B):
+        assert torch.all(got[b, int(sl[b]):] == 123.0)
+        assert not torch.isnan(got[b, : int(sl[b])]).any()
+
+
+@pytest.mark.parametrize("indexed", [False, True])
+def test_long_suffix_key_block_counts(lsp, oracle, indexed):
+    """Head_dim-128 long-suffix kernel (eight-stage ring, one barrier every four
+    key blocks): per-sequence key counts from 3 to 15 blocks, i.e. fewer blocks
+    than the prefetch depth, every remainder modulo the barrier period, ragged
+    last blocks, and a cache/suffix boundary inside a block; with the cache
+    addressed directly and through a shuffled row index."""
+    w = W.scaled(W.C2, B=8, S=160, P=320, C=320, Hq=32, Hkv=8, D=128, seed=123)
+    pl = torch.tensor([0, 1, 31, 33, 96, 100, 224, 320], dtype=torch.int32)
+    sl = torch.tensor([160, 95, 129, 130, 97, 160, 65, 160], dtype=torch.int32)   # all above the key-split switch
+    kv = W.make_layer_kv(w, 0, prefix_len=pl)
+    g = {k: v.cuda() for k, v in kv.items()}
+    index = None
+    if indexed:
+        gen = torch.Generator().manual_seed(5)
+        index = torch.stack([torch.randperm(w.C, generator=gen) for _ in range(w.B)]).to(torch.int32)
+        for name in ("k_cache", "v_cache"):
+            sh = torch.full_like(kv[name], float("nan"))
+            for b in range(w.B):
+                sh[b][index[b, : int(pl[b])].long()] = kv[name][b, : int(pl[b])]
+            g[name] = sh.cuda()
+    out = torch.full(g["q"].shape, 123.0, dtype=g["q"].dtype, device="cuda")
+    lsp.attn_step(g["q"], g["k_suf"], g["v_suf"], g["k_cache"], g["v_cache"], pl.cuda(), sl.cuda(), out=out,
+                  cache_row_index=None if index is None else index.cuda())
+    torch.cuda.synchronize()
+    got = out.float().cpu()
+    rows = torch.tensor([[b, i, h] for b in range(w.B) for i in range(int(sl[b])) for h in (0, 13, 31)
+                         if i < 2 or i >= int(sl[b]) - 2 or i % 31 == 0], dtype=torch.int32)
+    ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl, rows=rows)
+    sel = got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()]
+    assert (sel - ref).abs().max().item() <= TOL["bf16"]
     for b in range(w.B):
         assert torch.all(got[b, int(sl[b]):] == 123.0)
         assert not torch.isnan(got[b, : int(sl[b])]).any()
