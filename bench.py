@@ -35,10 +35,10 @@ MEASURED_TRAFFIC = {
     ("c2", "lsp_confidence"): (31695.3 * 2 + 24.0) * _KIB,
     ("c2", "lsp_attn_step"): (7263.6 * 2 + 2048.0) * _KIB,
     ("c2", "lsp_commit"): ((912.5 + 13.1) * 2 + 1796.0 + 0.9) * _KIB,
-    ("c3", "lsp_confidence"): (304201.9 * 2 + 192.0) * _KIB,
-    ("c3", "lsp_attn_step"): (13457.6 * 2 + 14376.2) * _KIB,
+    ("c3", "lsp_confidence"): (304202.0 * 2 + 192.0) * _KIB,
+    ("c3", "lsp_attn_step"): (13467.1 * 2 + 14415.0) * _KIB,
     ("c4", "lsp_confidence"): (1011782.7 * 2 + 773.0) * _KIB,
-    ("c4", "lsp_attn_step"): (360606.5 * 2 + 65539.6) * _KIB,
+    ("c4", "lsp_attn_step"): (360619.1 * 2 + 65538.7) * _KIB,
 }
 
 
