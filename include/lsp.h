@@ -90,7 +90,8 @@ size_t lsp_attn_workspace_bytes(const lsp_attn_desc *desc);
 
 /*
  * q, k_suf, v_suf, k_cache, v_cache, out: device, 16-byte aligned, strides
- * multiples of 16 bytes.  prefix_len, suffix_len: device int32[B], with
+ * multiples of 16 bytes; the row strides of the K/V buffers (suffix and cache)
+ * at most 2^24 elements.  prefix_len, suffix_len: device int32[B], with
  * 0 <= P_b <= C and 0 <= N_b <= S (not checked on the host; values are
  * clamped to those ranges on the device).  workspace: device, at least
  * lsp_attn_workspace_bytes(desc) bytes, 256-byte aligned (may be NULL when

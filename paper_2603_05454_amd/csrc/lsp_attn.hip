@@ -6,6 +6,8 @@
 namespace lsp {
 namespace {
 
+constexpr int64_t kMaxRowStride = int64_t(1) << 24;
+
 bool resolve(const int64_t in[3], int64_t out[3], int64_t rows, int64_t heads, int64_t D) {
   if (in[0] == 0 && in[1] == 0 && in[2] == 0) {
     out[2] = D;
@@ -32,6 +34,9 @@ int32_t check(const lsp_attn_desc *d, AttnArgs &a) {
                     resolve(d->cache_stride, a.cs, d->C, d->Hkv, d->D) &&
                     resolve(d->o_stride, a.os, d->S, d->Hq, d->D),
                 "lsp_attn: bad strides");
+  // the kernels keep byte offsets of up to 32 rows of a K/V block in 32 bits
+  LSP_CHECK_ARG(a.ks[1] <= kMaxRowStride && a.cs[1] <= kMaxRowStride,
+                "lsp_attn: K/V row strides above %lld elements are not supported", (long long)kMaxRowStride);
   const int64_t per16 = 16 / int64_t(elem_size(d->dtype));
   for (int k = 0; k < 3; ++k)
     LSP_CHECK_ARG(a.qs[k] % per16 == 0 && a.ks[k] % per16 == 0 && a.cs[k] % per16 == 0 && a.os[k] % per16 == 0,

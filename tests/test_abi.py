@@ -69,6 +69,9 @@ def test_argument_errors_are_reported_before_any_launch():
     sixteen = ctypes.c_void_p((ctypes.addressof(buf) + 15) & ~15)
     args = [sixteen] * 5 + [sixteen, sixteen, sixteen, None, ctypes.c_size_t(0), None]
     assert L.lsp_attn_step(ctypes.byref(d), *args) == -2 and b"head_dim" in L.lsp_last_error()
+    d = lsp.AttnDesc(dtype=1, B=1, S=4, Hq=2, Hkv=2, D=128, C=8)
+    d.cache_stride[0], d.cache_stride[1], d.cache_stride[2] = 8 << 25, 1 << 25, 128
+    assert L.lsp_attn_step(ctypes.byref(d), *args) == -1 and b"row strides" in L.lsp_last_error()
 
     # output head: dtype, K granularity, strides, workspace (all before any launch)
     i64 = ctypes.c_int64
