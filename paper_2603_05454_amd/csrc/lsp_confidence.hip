@@ -371,19 +371,23 @@ __global__ void confidence_finish_kernel(const Partial *__restrict__ partials, i
   top1_prob[o] = 1.0f / a.s;
 }
 
-// Launch shape (measured on MI355X).  One wave per row streams best once there
-// are thousands of rows (no barrier, finest-grained scheduling); with fewer
-// rows the workgroup widens so that about 2048 waves are in flight, and below
-// that rows are also cut into segments reduced by separate workgroups.  More
-// waves or more vectors per lane than this did not help: per element the
-// kernel issues about nine VALU cycles (the exponential counts four), which at
-// these sizes is as long as the memory time itself.
+// Launch shape (measured on MI355X).  A workgroup takes a row; it is as wide as
+// leaves each lane about 64 vectors of 16 bytes (one wave for rows of a few
+// thousand entries, four waves for a 126 464-entry bf16 row: 2-7 % faster there
+// than one wave per row, and a 512-thread workgroup is 3x slower on 4 096-entry
+// rows); with few rows it widens further so that at least 2048 waves are in
+// flight, and below that rows are also cut into segments reduced by separate
+// workgroups.  Per element the kernel issues about nine VALU cycles (the
+// exponential counts four), which at these sizes is as long as the memory time
+// itself.
 struct Plan {
   int nt, splits, seg_elems;
 };
-inline Plan plan(int64_t rows, int V) {
+inline Plan plan(int64_t rows, int V, int elem_bytes) {
   Plan p;
   int nt = 64;
+  const int64_t nvec = int64_t(V) * elem_bytes / 16;
+  while (nt < 512 && nvec / nt >= 96) nt *= 2;
   while (nt < 512 && rows * (nt / 64) < 2048) nt *= 2;
 #ifdef LSP_TUNE
   if (getenv("LSP_CONF_NT")) nt = atoi(getenv("LSP_CONF_NT"));
@@ -434,8 +438,10 @@ void launch_confidence(const Plan &p, dim3 grid, hipStream_t st, const T *z, int
 
 extern "C" size_t lsp_confidence_workspace_bytes(int32_t B, int32_t S, int32_t V) {
   if (B <= 0 || S <= 0 || V <= 0) return 0;
-  const lsp::Plan p = lsp::plan(int64_t(B) * S, V);
-  return p.splits > 1 ? size_t(B) * S * p.splits * sizeof(lsp::Partial) : 0;
+  // the dtype is not an argument here: enough for either
+  const int s2 = lsp::plan(int64_t(B) * S, V, 2).splits, s4 = lsp::plan(int64_t(B) * S, V, 4).splits;
+  const int splits = s2 > s4 ? s2 : s4;
+  return splits > 1 ? size_t(B) * S * splits * sizeof(lsp::Partial) : 0;
 }
 
 extern "C" int32_t lsp_confidence(int32_t dtype, const void *logits, int32_t B, int32_t S, int32_t V,
@@ -453,7 +459,7 @@ extern "C" int32_t lsp_confidence(int32_t dtype, const void *logits, int32_t B, 
   LSP_CHECK_ARG(row_stride >= V && batch_stride >= 0, "lsp_confidence: bad strides");
   const size_t es = elem_size(dtype);
   LSP_CHECK_ARG((reinterpret_cast<uintptr_t>(logits) & (es - 1)) == 0, "lsp_confidence: logits misaligned");
-  const Plan p = plan(int64_t(B) * S, V);
+  const Plan p = plan(int64_t(B) * S, V, int(es));
   const size_t need = p.splits > 1 ? size_t(B) * S * p.splits * sizeof(Partial) : 0;
   if (need > 0 && (workspace == nullptr || workspace_bytes < need ||
                    (reinterpret_cast<uintptr_t>(workspace) & 15u))) {
