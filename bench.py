@@ -32,13 +32,13 @@ MALL_BYTES = 256 << 20
 # (workload, call) -> read + written bytes.  None where no counter run has been made.
 _KIB = 1024
 MEASURED_TRAFFIC = {
-    ("c2", "lsp_confidence"): (31695.3 * 2 + 24.0) * _KIB,
-    ("c2", "lsp_attn_step"): (7263.6 * 2 + 2048.0) * _KIB,
+    ("c2", "lsp_confidence"): (31693.7 * 2 + 24.0) * _KIB,
+    ("c2", "lsp_attn_step"): (7262.1 * 2 + 2048.0) * _KIB,
     ("c2", "lsp_commit"): ((912.5 + 13.1) * 2 + 1796.0 + 0.9) * _KIB,
-    ("c3", "lsp_confidence"): (304202.0 * 2 + 192.0) * _KIB,
-    ("c3", "lsp_attn_step"): (13467.1 * 2 + 14415.0) * _KIB,
-    ("c4", "lsp_confidence"): (1011782.7 * 2 + 773.0) * _KIB,
-    ("c4", "lsp_attn_step"): (360619.1 * 2 + 65538.7) * _KIB,
+    ("c3", "lsp_confidence"): (304247.0 * 2 + 192.3) * _KIB,
+    ("c3", "lsp_attn_step"): (13467.1 * 2 + 14416.2) * _KIB,
+    ("c4", "lsp_confidence"): (1011977.1 * 2 + 770.1) * _KIB,
+    ("c4", "lsp_attn_step"): (360623.2 * 2 + 65554.4) * _KIB,
 }
 
 
