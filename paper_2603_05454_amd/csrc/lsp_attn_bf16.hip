@@ -853,6 +853,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int lq = lane & 31, hf = lane >> 5;
 
+  // A wave none of whose 32 queries is active (the last tile of a sequence) only
+  // fetches its share of the K/V blocks and keeps the barriers: the wave that
+  // shares its SIMD then has the matrix and vector pipes to itself.
+  const bool live = q0 + 32 * wave_s < N;
   const int qi = q0 + wave * 32 + lq;
   const uint16_t *qp = static_cast<const uint16_t *>(a.q) + b * a.qs[0] + int64_t(min(qi, N - 1)) * a.qs[1] + h * a.qs[2];
   bf16x8 qf[KK];
@@ -941,21 +945,23 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       if (jb >= NB) break;
       // the stage that block jb-BS was read from is free since the last barrier
       LSP_RING_ISSUE(min(jb + NS - BS, NB - 1), (u + NS - BS) % NS);
-      bf16x8 kf[KK];
+      if (live) {
+        bf16x8 kf[KK];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) kf[kk] = *reinterpret_cast<const bf16x8 *>(kaddr[kk] + u * TILE);
-      f32x16 s;
+        for (int kk = 0; kk < KK; ++kk) kf[kk] = *reinterpret_cast<const bf16x8 *>(kaddr[kk] + u * TILE);
+        f32x16 s;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
-      bf16x8 vf[DB][2];
+        for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
+        bf16x8 vf[DB][2];
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2) vf[db][k2] = vt_read<D * 2>(vaddr[db] + u * TILE + (16 * k2) * (D * 2));
-      __builtin_amdgcn_sched_barrier(0);
-      softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, vf);
+          for (int k2 = 0; k2 < 2; ++k2) vf[db][k2] = vt_read<D * 2>(vaddr[db] + u * TILE + (16 * k2) * (D * 2));
+        __builtin_amdgcn_sched_barrier(0);
+        softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, vf);
+      }
       if ((u % BS) == BS - 1) {
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(kWaitRing);  // blocks jb+1 .. jb+BS have landed
