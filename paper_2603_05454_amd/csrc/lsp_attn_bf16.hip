@@ -614,6 +614,9 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
   const uint16_t *ks = static_cast<const uint16_t *>(a.k_suf) + b * a.ks[0] + g * a.ks[2];
   const uint16_t *vs = static_cast<const uint16_t *>(a.v_suf) + b * a.ks[0] + g * a.ks[2];
 
+  // a wave none of whose 32 queries is active only fetches its share of the K/V
+  // blocks and keeps the barriers
+  const bool live = q0 + 32 * __builtin_amdgcn_readfirstlane(wave) < N;
   const int qi = q0 + wave * 32 + lq;
   const uint16_t *qp = static_cast<const uint16_t *>(a.q) + b * a.qs[0] + int64_t(min(qi, N - 1)) * a.qs[1] + h * a.qs[2];
   bf16x8 qf[KK];
@@ -712,21 +715,25 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
       // the exponentials run); soft-max; second product.
       const unsigned char *st = smem + (jb & 1) * TG::STAGE;
       bf16x8 kf[KK];
+      if (live) {
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-        kf[kk] = *reinterpret_cast<const bf16x8 *>(st + lq * TG::KPITCH + (16 * kk + 8 * hf) * 2);
+        for (int kk = 0; kk < KK; ++kk)
+          kf[kk] = *reinterpret_cast<const bf16x8 *>(st + lq * TG::KPITCH + (16 * kk + 8 * hf) * 2);
+      }
       __builtin_amdgcn_sched_barrier(0);
       if (jb + 1 < NB) store_block(jb + 1, kreg[u], vreg[u]);
       if (jb + 1 + PD < NB) load_block(jb + 1 + PD, kreg[u], vreg[u]);
-      f32x16 s;
+      if (live) {
+        f32x16 s;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
-      bf16x8 vf[DB][2];
-      load_v_frags<D>(vf, lane, st + TG::KBYTES);
-      __builtin_amdgcn_sched_barrier(0);
-      softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, vf);
+        for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
+        bf16x8 vf[DB][2];
+        load_v_frags<D>(vf, lane, st + TG::KBYTES);
+        __builtin_amdgcn_sched_barrier(0);
+        softmax_pv<D>(s, oacc, mref, lsum, 32 * jb, T, sc, lane, vf);
+      }
       __syncthreads();
     }
   }
