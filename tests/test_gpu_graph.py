@@ -16,10 +16,12 @@ def lsp():
     return m
 
 
-@pytest.mark.parametrize("cfg", ["split_rows", "many_rows"])
+@pytest.mark.parametrize("cfg", ["split_rows", "many_rows", "long_suffix"])
 def test_graph_replays_match_eager(lsp, cfg):
     if cfg == "split_rows":      # few rows: confidence splits rows over workgroups and uses its workspace
         w = W.scaled(W.C2, B=2, S=24, P=40, C=96, Hq=4, Hkv=2, D=128, V=70001, layers=2)
+    elif cfg == "long_suffix":   # enough (sequence, head, row) triples for the long-suffix attention kernel
+        w = W.scaled(W.C3, B=8, S=160, P=200, C=512, Hq=32, Hkv=8, D=128, V=4099, layers=2)
     else:
         w = W.scaled(W.C3, B=3, S=300, P=200, C=512, Hq=8, Hkv=2, D=128, V=4099, layers=2)
     dev = "cuda"
