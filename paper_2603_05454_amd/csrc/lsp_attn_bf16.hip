@@ -22,7 +22,7 @@
 // probabilities are then at most 2^8, which bf16 and the fp32 sums hold
 // without loss, and the final division by the row sum removes the offset.
 //
-// Two kernels share that arithmetic:
+// Three kernels share that arithmetic:
 //  * attn_bf16_kernel (short suffixes): a workgroup is WM x WK waves, WM blocks
 //    of 32 queries and a WK-way split of the key range between waves of the
 //    same query block (merged through LDS at the end).  Every wave streams its
@@ -34,10 +34,10 @@
 //    each K/V block through a two-stage LDS ring (every wave fetches 1/WM of
 //    the block), one barrier per block; L1/L2 traffic per flop drops WM-fold,
 //    which is what the matrix cores need once the problem is compute bound.
-// and, for head_dim 128 and suffix buffers of more than 128 rows, a third form of
-// the long-suffix kernel, attn_bf16_ring_kernel (eight waves, K/V straight from
-// global memory into an eight-stage LDS ring, one barrier every four blocks),
-// described where it is defined.
+//  * attn_bf16_ring_kernel (long suffixes at head_dim 128 with suffix buffers of
+//    more than 128 rows): eight waves, K/V straight from global memory into an
+//    eight-stage LDS ring, one barrier every four blocks; described where it is
+//    defined.
 #include "lsp_attn.h"
 #ifdef LSP_TUNE
 #include <stdlib.h>
