@@ -1,6 +1,6 @@
 """GPU parity on seeded random shapes: every entry point against the CPU oracle
 on a few hundred small problems whose sizes, lengths, strides and parameters are
-drawn at random (Algorithm 1 lines 4-10; Eq. 1; Eq. 2).  The fixed cases of the
+drawn at random (Algorithm 1 lines 4-10; Eq. 1; Eq. 2; Section 4.3.3).  The fixed cases of the
 other files aim at known edges; this file covers combinations nobody thought of.
 All sizes stay inside the documented limits of the entry points.
 
@@ -163,8 +163,49 @@ def _lm_head_trial(lsp, oracle, rng):
     tl._compare(got, ref[:3], ref[3])
 
 
+def _scattered_trial(lsp, oracle, rng):
+    """Section 4.3.3's comparison pieces: top-k selection by margin, then the gathered append."""
+    B, S = rng.randint(1, 9), rng.choice([1, 5, 64, 65, 257, 700, 1024, 2000])
+    g = torch.Generator().manual_seed(rng.randint(0, 10**6))
+    margin = torch.rand((B, S), generator=g)
+    if rng.random() < 0.4:
+        margin = (margin * rng.choice([2, 4, 16])).floor() / 16   # ties: the lower position wins
+    sl = torch.tensor([rng.choice([0, 1, S, rng.randint(0, S)]) for _ in range(B)], dtype=torch.int32)
+    ct = torch.tensor([rng.choice([0, 1, S, rng.randint(0, S)]) for _ in range(B)], dtype=torch.int32)
+    case = f"scattered B={B} S={S} sl={sl.tolist()} ct={ct.tolist()}"
+    ri, rm = oracle.select_scattered(margin, sl, ct)
+    gi, gm = lsp.select_scattered(margin.cuda(), sl.cuda(), ct.cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(gi.cpu(), ri) and torch.equal(gm.cpu(), rm), case
+    if S > 300:
+        return
+    nl, Hkv, D = rng.choice([1, 3]), rng.choice([1, 2]), rng.choice([64, 128])
+    dt = rng.choice([torch.bfloat16, torch.float32])
+    C = rng.choice([S, S + 37, 64])
+    pl = torch.tensor([rng.randint(0, C) for _ in range(B)], dtype=torch.int32)
+    layers = [dict(k_suf=torch.randn((B, S, Hkv, D), generator=g).to(dt), v_suf=torch.randn((B, S, Hkv, D), generator=g).to(dt),
+                   k_cache=torch.randn((B, C, Hkv, D), generator=g).to(dt), v_cache=torch.randn((B, C, Hkv, D), generator=g).to(dt))
+              for _ in range(nl)]
+    cnt = torch.minimum(ct, sl)
+    ref = [{k: v.clone() for k, v in L.items()} for L in layers]
+    pl_r = pl.clone()
+    oracle.gather_append(ri, cnt, pl_r, [L["k_suf"] for L in ref], [L["v_suf"] for L in ref],
+                         [L["k_cache"] for L in ref], [L["v_cache"] for L in ref])
+    dev = [{k: v.cuda() for k, v in L.items()} for L in layers]
+    table = lsp.LayerTable([L["k_suf"] for L in dev], [L["v_suf"] for L in dev], [L["k_cache"] for L in dev],
+                           [L["v_cache"] for L in dev])
+    pl_g = pl.cuda()
+    app = lsp.kv_gather_append(gi, cnt.cuda(), pl_g, table)
+    torch.cuda.synchronize()
+    assert torch.equal(pl_g.cpu(), pl_r) and app.cpu().tolist() == (pl_r - pl).tolist(), case
+    view = torch.int16 if dt == torch.bfloat16 else torch.int32
+    for Lg, Lr in zip(dev, ref):
+        for name in ("k_cache", "v_cache"):
+            assert torch.equal(Lg[name].cpu().view(view), Lr[name].view(view)), (case, name)
+
+
 TRIALS = {"attention": (_attention_trial, 150), "confidence": (_confidence_trial, 150),
-          "commit": (_commit_trial, 150), "lm_head": (_lm_head_trial, 60)}
+          "commit": (_commit_trial, 150), "lm_head": (_lm_head_trial, 60), "scattered": (_scattered_trial, 100)}
 
 
 @pytest.mark.parametrize("name", list(TRIALS))
