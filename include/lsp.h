@@ -127,6 +127,27 @@ int32_t lsp_confidence(int32_t dtype, const void *logits, int32_t B, int32_t S, 
                        int32_t *top1_id, float *top1_prob, float *margin,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * lsp_confidence for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and launches as lsp_confidence,
+ * but the per-segment results of split rows (the only scratch that call needs:
+ * rows are split when B*S < 128) go to a buffer of
+ * lsp_confidence_static_scratch_bytes() = 65536 bytes that is part of the
+ * library's device image; each GPU the library runs on holds its own copy until
+ * the process ends.  The call allocates and frees nothing (its first use on a
+ * GPU looks up the buffer's address).  A shape whose launch plan needs more
+ * than the buffer holds returns LSP_ERR_UNSUPPORTED and launches nothing.
+ * Every call on one GPU shares that GPU's buffer: calls whose execution may
+ * overlap on one GPU (different streams, or several host threads) race; calls
+ * in stream order on one stream do not.  Nothing has to be cleared between
+ * calls (every value read was written by the same call).
+ */
+size_t lsp_confidence_static_scratch_bytes(void);
+int32_t lsp_confidence_static(int32_t dtype, const void *logits, int32_t B, int32_t S, int32_t V,
+                              int64_t row_stride, int64_t batch_stride, const int32_t *suffix_len,
+                              int32_t *top1_id, float *top1_prob, float *margin, void *stream);
+
 /* ------------------------------------------------------------------------- *
  * Boundary search, snap, commit and append (Section 3.2: L'(tau), the snap
  * equation and the monotone-progress fallback; Algorithm 1 lines 7-10).

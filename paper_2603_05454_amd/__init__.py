@@ -44,7 +44,8 @@ class CommitDesc(ctypes.Structure):
 
 
 EXPORTS = ["lsp_version", "lsp_last_error", "lsp_attn_workspace_bytes", "lsp_attn_step",
-           "lsp_confidence_workspace_bytes", "lsp_confidence", "lsp_commit_workspace_bytes",
+           "lsp_confidence_workspace_bytes", "lsp_confidence", "lsp_confidence_static_scratch_bytes",
+           "lsp_confidence_static", "lsp_commit_workspace_bytes",
            "lsp_commit", "lsp_flip_update", "lsp_select_scattered", "lsp_kv_gather_append",
            "lsp_attn_step_gather", "lsp_lm_head_confidence_workspace_bytes", "lsp_lm_head_confidence"]
 
@@ -60,9 +61,9 @@ def lib() -> ctypes.CDLL:
         L.lsp_version.restype = ctypes.c_char_p
         L.lsp_last_error.restype = ctypes.c_char_p
         for n in ("lsp_attn_workspace_bytes", "lsp_confidence_workspace_bytes", "lsp_commit_workspace_bytes",
-                  "lsp_lm_head_confidence_workspace_bytes"):
+                  "lsp_lm_head_confidence_workspace_bytes", "lsp_confidence_static_scratch_bytes"):
             getattr(L, n).restype = ctypes.c_size_t
-        for n in ("lsp_attn_step", "lsp_confidence", "lsp_commit", "lsp_flip_update", "lsp_select_scattered",
+        for n in ("lsp_attn_step", "lsp_confidence", "lsp_confidence_static", "lsp_commit", "lsp_flip_update", "lsp_select_scattered",
                   "lsp_kv_gather_append", "lsp_attn_step_gather", "lsp_lm_head_confidence"):
             getattr(L, n).restype = ctypes.c_int32
         _lib = L
@@ -168,6 +169,19 @@ def confidence(logits, suffix_len=None, out=None, workspace=None):
                               _ptr(suffix_len), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]),
                               _ptr(workspace), ctypes.c_size_t(wb), _stream())
     _check(rc, "lsp_confidence")
+    return out
+
+
+def confidence_static(logits, suffix_len, out):
+    """lsp_confidence_static: lsp_confidence without a workspace and without any
+    allocation; `out` = (top1_id int32, top1_prob f32, margin f32), [B,S], is required."""
+    _dev(logits, suffix_len, *out)
+    B, S, V = logits.shape
+    assert logits.stride(2) == 1
+    rc = lib().lsp_confidence_static(_dtype(logits), _ptr(logits), B, S, V,
+                                     ctypes.c_int64(logits.stride(1)), ctypes.c_int64(logits.stride(0)),
+                                     _ptr(suffix_len), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream())
+    _check(rc, "lsp_confidence_static")
     return out
 
 

@@ -28,6 +28,7 @@
 #include <float.h>
 #include <limits.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "lsp_common.h"
@@ -444,31 +445,46 @@ extern "C" size_t lsp_confidence_workspace_bytes(int32_t B, int32_t S, int32_t V
   return splits > 1 ? size_t(B) * S * splits * sizeof(lsp::Partial) : 0;
 }
 
-extern "C" int32_t lsp_confidence(int32_t dtype, const void *logits, int32_t B, int32_t S, int32_t V,
-                                  int64_t row_stride, int64_t batch_stride,
-                                  const int32_t *suffix_len, int32_t *top1_id, float *top1_prob,
-                                  float *margin, void *workspace, size_t workspace_bytes,
-                                  void *stream) {
-  using namespace lsp;
-  LSP_CHECK_ARG(dtype == LSP_F32 || dtype == LSP_BF16, "lsp_confidence: unknown dtype %d", dtype);
-  LSP_CHECK_ARG(logits && top1_id && top1_prob && margin, "lsp_confidence: null pointer");
-  LSP_CHECK_ARG(B > 0 && S > 0 && V >= 2, "lsp_confidence: need B>0, S>0, V>=2 (got %d %d %d)", B, S, V);
-  LSP_CHECK_ARG(B <= 65535 && S <= 65535, "lsp_confidence: B and S must be <= 65535");
+namespace lsp {
+namespace {
+
+int32_t scratch_address(void **out);  // device address of the library's own scratch buffer (defined below)
+
+// Host side shared by both entry points: validation, launch plan, launches.
+// `parts` is where split rows leave their per-segment results (`parts_bytes`
+// available); `who` names the entry point in error texts and `fixed_scratch`
+// says that the buffer is the library's own (a different error then).
+int32_t confidence_run(const char *who, bool fixed_scratch, int32_t dtype, const void *logits, int32_t B,
+                       int32_t S, int32_t V, int64_t row_stride, int64_t batch_stride,
+                       const int32_t *suffix_len, int32_t *top1_id, float *top1_prob, float *margin,
+                       void *parts_mem, size_t parts_bytes, void *stream) {
+  LSP_CHECK_ARG(dtype == LSP_F32 || dtype == LSP_BF16, "%s: unknown dtype %d", who, dtype);
+  LSP_CHECK_ARG(logits && top1_id && top1_prob && margin, "%s: null pointer", who);
+  LSP_CHECK_ARG(B > 0 && S > 0 && V >= 2, "%s: need B>0, S>0, V>=2 (got %d %d %d)", who, B, S, V);
+  LSP_CHECK_ARG(B <= 65535 && S <= 65535, "%s: B and S must be <= 65535", who);
   if (row_stride == 0) row_stride = V;
   if (batch_stride == 0) batch_stride = int64_t(S) * row_stride;
-  LSP_CHECK_ARG(row_stride >= V && batch_stride >= 0, "lsp_confidence: bad strides");
+  LSP_CHECK_ARG(row_stride >= V && batch_stride >= 0, "%s: bad strides", who);
   const size_t es = elem_size(dtype);
-  LSP_CHECK_ARG((reinterpret_cast<uintptr_t>(logits) & (es - 1)) == 0, "lsp_confidence: logits misaligned");
+  LSP_CHECK_ARG((reinterpret_cast<uintptr_t>(logits) & (es - 1)) == 0, "%s: logits misaligned", who);
   const Plan p = plan(int64_t(B) * S, V, int(es));
   const size_t need = p.splits > 1 ? size_t(B) * S * p.splits * sizeof(Partial) : 0;
-  if (need > 0 && (workspace == nullptr || workspace_bytes < need ||
-                   (reinterpret_cast<uintptr_t>(workspace) & 15u))) {
-    set_error("lsp_confidence: workspace of %zu bytes (16-byte aligned) required, got %zu", need, workspace_bytes);
+  if (need > 0 && fixed_scratch && parts_bytes < need) {
+    set_error("%s: this shape needs %zu bytes of scratch, the built-in buffer holds %zu; use lsp_confidence "
+              "with a workspace", who, need, parts_bytes);
+    return LSP_ERR_UNSUPPORTED;
+  }
+  if (fixed_scratch) {  // looked up only after the arguments have passed validation
+    const int32_t rc = scratch_address(&parts_mem);
+    if (rc != LSP_OK) return rc;
+  }
+  if (need > 0 && (parts_mem == nullptr || parts_bytes < need || (reinterpret_cast<uintptr_t>(parts_mem) & 15u))) {
+    set_error("%s: workspace of %zu bytes (16-byte aligned) required, got %zu", who, need, parts_bytes);
     return LSP_ERR_WORKSPACE;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
   const dim3 grid(p.splits, S, B);
-  Partial *parts = static_cast<Partial *>(workspace);
+  Partial *parts = static_cast<Partial *>(parts_mem);
   if (dtype == LSP_BF16)
     launch_confidence<uint16_t>(p, grid, st, static_cast<const uint16_t *>(logits), S, V, row_stride,
                                 batch_stride, suffix_len, top1_id, top1_prob, margin, parts);
@@ -482,4 +498,64 @@ extern "C" int32_t lsp_confidence(int32_t dtype, const void *logits, int32_t B, 
     LSP_CHECK_LAUNCH("lsp_confidence: finish launch");
   }
   return LSP_OK;
+}
+
+}  // namespace
+}  // namespace lsp
+
+extern "C" int32_t lsp_confidence(int32_t dtype, const void *logits, int32_t B, int32_t S, int32_t V,
+                                  int64_t row_stride, int64_t batch_stride,
+                                  const int32_t *suffix_len, int32_t *top1_id, float *top1_prob,
+                                  float *margin, void *workspace, size_t workspace_bytes,
+                                  void *stream) {
+  return lsp::confidence_run("lsp_confidence", false, dtype, logits, B, S, V, row_stride, batch_stride,
+                             suffix_len, top1_id, top1_prob, margin, workspace, workspace_bytes, stream);
+}
+
+// ---- the same call for callers that cannot allocate ----------------------------
+// The per-segment results of split rows go to a buffer that is part of the
+// library's device image instead of a caller-provided workspace.  Rows are only
+// split when there are fewer than 128 of them, into at most 32 segments of 16
+// bytes each, so 64 KB cover every shape the launch plan can produce.
+#define LSP_CONF_SCRATCH_BYTES 65536
+static __device__ __align__(256) unsigned char scratch[LSP_CONF_SCRATCH_BYTES];
+
+namespace lsp {
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU (every GPU has its own copy)
+
+// Device address of the scratch array on the current GPU, looked up once per GPU.
+int32_t scratch_address(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "lsp_confidence_static: hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) {
+    set_error("lsp_confidence_static: device ordinal %d not supported (< %d)", dev, kMaxDevices);
+    return LSP_ERR_UNSUPPORTED;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) return hip_fail(e, "lsp_confidence_static: hipGetSymbolAddress");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LSP_OK;
+}
+}  // namespace
+}  // namespace lsp
+
+extern "C" size_t lsp_confidence_static_scratch_bytes(void) { return LSP_CONF_SCRATCH_BYTES; }
+
+extern "C" int32_t lsp_confidence_static(int32_t dtype, const void *logits, int32_t B, int32_t S, int32_t V,
+                                         int64_t row_stride, int64_t batch_stride,
+                                         const int32_t *suffix_len, int32_t *top1_id, float *top1_prob,
+                                         float *margin, void *stream) {
+  // Every segment result that the second kernel reads is written by the first
+  // kernel of the same call, so nothing has to be cleared between calls.
+  return lsp::confidence_run("lsp_confidence_static", true, dtype, logits, B, S, V, row_stride, batch_stride,
+                             suffix_len, top1_id, top1_prob, margin, nullptr, LSP_CONF_SCRATCH_BYTES, stream);
 }
