@@ -312,13 +312,20 @@ int32_t lsp_lm_head_confidence(int32_t dtype, const void *hidden, const void *we
  * [B,G] holds, per generation position (0 = first generated token), the top-1
  * id it had at the previous step, or -1.  With done_b = prefix_len[b] -
  * base_prefix_len[b], for u < N_b: position j = done_b + u; if last_id[b,j] >=
- * 0 then counters[1] += 1 and counters[0] += (last_id[b,j] != top1_id[b,u]);
- * then last_id[b,j] = top1_id[b,u].  counters: device int64[2] accumulated.
+ * 0 the position is compared (it counts as a flip when last_id[b,j] !=
+ * top1_id[b,u]); then last_id[b,j] = top1_id[b,u].
+ * counters: device int64[4], accumulated: [0] flips, [1] positions compared,
+ * [2] and [3] the same restricted to sequences with window_lo <= done_b <=
+ * window_hi (the paper quotes the rate for the mid-stage of generation, 25-75 %
+ * complete; pass window_lo > window_hi for no window).
+ * step_counts: device int32 [B,2] or NULL; when given, this call's flips and
+ * compared positions of every sequence are WRITTEN there (a per-step trace).
  * ------------------------------------------------------------------------- */
 int32_t lsp_flip_update(const int32_t *top1_id, int32_t B, int32_t S, int32_t G,
                         const int32_t *prefix_len, const int32_t *suffix_len,
                         const int32_t *base_prefix_len, int32_t *last_id,
-                        int64_t *counters, void *stream);
+                        int64_t *counters, int32_t window_lo, int32_t window_hi,
+                        int32_t *step_counts, void *stream);
 
 #ifdef __cplusplus
 }

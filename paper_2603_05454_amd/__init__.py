@@ -272,12 +272,17 @@ def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
     return out
 
 
-def flip_update(top1_id, prefix_len, suffix_len, base_prefix_len, last_id, counters):
-    """lsp_flip_update: accumulate counters (int64[2]: flips, positions compared)."""
-    _dev(top1_id, prefix_len, suffix_len, base_prefix_len, last_id, counters)
+def flip_update(top1_id, prefix_len, suffix_len, base_prefix_len, last_id, counters, window=None, step_counts=None):
+    """lsp_flip_update: accumulate counters (int64[4]: flips, positions compared, and the
+    same two for sequences whose committed count lies in window = (lo, hi), inclusive);
+    step_counts int32 [B,2], when given, receives this call's per-sequence counts."""
+    _dev(top1_id, prefix_len, suffix_len, base_prefix_len, last_id, counters, step_counts)
     B, S = top1_id.shape
+    assert counters.numel() == 4 and counters.dtype == torch.int64
+    lo, hi = (1, 0) if window is None else window
     rc = lib().lsp_flip_update(_ptr(top1_id), B, S, last_id.shape[1], _ptr(prefix_len), _ptr(suffix_len),
-                               _ptr(base_prefix_len), _ptr(last_id), _ptr(counters), _stream())
+                               _ptr(base_prefix_len), _ptr(last_id), _ptr(counters), int(lo), int(hi),
+                               _ptr(step_counts), _stream())
     _check(rc, "lsp_flip_update")
 
 

@@ -17,14 +17,20 @@ void set_error(const char *fmt, ...) {
 namespace {
 
 // Section 4.3.4 flip bookkeeping: one workgroup per sequence; a position counts
-// when it already had a prediction at the previous step.
+// when it already had a prediction at the previous step.  The sequence's counts
+// also go to the mid-generation window when the number of its positions already
+// committed lies in [window_lo, window_hi].
 __global__ __launch_bounds__(256) void flip_kernel(
     const int32_t *__restrict__ top1_id, int S, int G, const int32_t *__restrict__ prefix_len,
     const int32_t *__restrict__ suffix_len, const int32_t *__restrict__ base_prefix_len,
-    int32_t *__restrict__ last_id, unsigned long long *__restrict__ counters) {
+    int32_t *__restrict__ last_id, unsigned long long *__restrict__ counters, int window_lo,
+    int window_hi, int32_t *__restrict__ step_counts) {
+  __shared__ int total[2];
   const int b = blockIdx.x;
   const int N = min(max(suffix_len[b], 0), S);
   const int done = prefix_len[b] - base_prefix_len[b];
+  if (threadIdx.x < 2) total[threadIdx.x] = 0;
+  __syncthreads();
   int flips = 0, seen = 0;
   for (int u = threadIdx.x; u < N; u += blockDim.x) {
     const int j = done + u;
@@ -43,8 +49,22 @@ __global__ __launch_bounds__(256) void flip_kernel(
     seen += __shfl_xor(seen, m);
   }
   if ((threadIdx.x & (kWave - 1)) == 0 && seen > 0) {
-    atomicAdd(&counters[0], (unsigned long long)flips);
-    atomicAdd(&counters[1], (unsigned long long)seen);
+    atomicAdd(&total[0], flips);
+    atomicAdd(&total[1], seen);
+  }
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  if (step_counts != nullptr) {
+    step_counts[2 * b] = total[0];
+    step_counts[2 * b + 1] = total[1];
+  }
+  if (total[1] > 0) {
+    atomicAdd(&counters[0], (unsigned long long)total[0]);
+    atomicAdd(&counters[1], (unsigned long long)total[1]);
+    if (done >= window_lo && done <= window_hi) {
+      atomicAdd(&counters[2], (unsigned long long)total[0]);
+      atomicAdd(&counters[3], (unsigned long long)total[1]);
+    }
   }
 }
 
@@ -57,14 +77,15 @@ extern "C" const char *lsp_last_error(void) { return lsp::g_error; }
 extern "C" int32_t lsp_flip_update(const int32_t *top1_id, int32_t B, int32_t S, int32_t G,
                                    const int32_t *prefix_len, const int32_t *suffix_len,
                                    const int32_t *base_prefix_len, int32_t *last_id,
-                                   int64_t *counters, void *stream) {
+                                   int64_t *counters, int32_t window_lo, int32_t window_hi,
+                                   int32_t *step_counts, void *stream) {
   using namespace lsp;
   LSP_CHECK_ARG(top1_id && prefix_len && suffix_len && base_prefix_len && last_id && counters,
                 "lsp_flip_update: null pointer");
   LSP_CHECK_ARG(B > 0 && S > 0 && G > 0, "lsp_flip_update: bad B/S/G");
   flip_kernel<<<B, 256, 0, static_cast<hipStream_t>(stream)>>>(
       top1_id, S, G, prefix_len, suffix_len, base_prefix_len, last_id,
-      reinterpret_cast<unsigned long long *>(counters));
+      reinterpret_cast<unsigned long long *>(counters), window_lo, window_hi, step_counts);
   LSP_CHECK_LAUNCH("lsp_flip_update: launch");
   return LSP_OK;
 }

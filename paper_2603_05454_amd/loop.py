@@ -10,14 +10,14 @@ from __future__ import annotations
 
 import torch
 
-from . import (LayerTable, attn_step, commit, confidence, flip_update, lm_head_confidence,
+from . import (LayerTable, LspError, attn_step, commit, confidence, flip_update, lm_head_confidence,
                lm_head_confidence_workspace_bytes)
 
 
 def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
                 prefix_len, suffix_len, tokens, kv_layers=None, gen_len=None, run_attention=False,
                 poll=1, max_steps=100000, stop_after=None, observer=None, timed=False, commit_kw=None,
-                graph=False, lm_head_weight=None):
+                graph=False, lm_head_weight=None, flip_window=None, flip_trace=False):
     """logits_fn(step, prefix_len) -> device logits [B,S,V].  prefix_len,
     suffix_len, tokens and the caches in kv_layers (list of dicts q?, k_suf,
     v_suf, k_cache, v_cache) are updated in place.
@@ -35,13 +35,26 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     host, so the same graph serves every step); the first step runs eagerly.
     The step's logits must then sit at one address: a tensor that logits_fn
     returns elsewhere is copied there (outside the timed region).
-    Returns dict(steps, flips, flip_denominator, committed[, lsp_ms, lsp_ms_steps])."""
+    flip_window: (lo, hi) committed positions of a sequence, inclusive, inside which its
+    flips also count towards the mid-generation window of Section 4.3.4 (default: 25 %-75 %
+    of the generation length).  flip_trace: keep every step's per-sequence counts.
+    A sequence that still has active positions but commits nothing (min_commit = 0, or its
+    cache / token buffer is full) would never finish: the loop raises LspError instead.
+    Returns dict(steps, flips, flip_denominator, window_flips, window_denominator, committed
+    [, flip_trace: int32 [steps,B,2]][, lsp_ms, lsp_ms_steps])."""
     dev = prefix_len.device
     B = prefix_len.shape[0]
     G = int(gen_len if gen_len is not None else suffix_len.max().item())
     base = prefix_len.clone()
     last_id = torch.full((B, G), -1, dtype=torch.int32, device=dev)
-    counters = torch.zeros(2, dtype=torch.int64, device=dev)
+    counters = torch.zeros(4, dtype=torch.int64, device=dev)
+    if flip_window is None:
+        flip_window = (-(-G // 4), (3 * G) // 4)
+    step_counts = torch.zeros((B, 2), dtype=torch.int32, device=dev) if flip_trace else None
+    trace = []
+    if min_commit < 1 and stop_after is None:
+        raise LspError("decode_loop needs min_commit >= 1 (Section 3.2: at least one token per iteration) "
+                       "unless stop_after bounds the number of steps")
     table = None
     if kv_layers is not None:
         table = LayerTable([L["k_suf"] for L in kv_layers], [L["v_suf"] for L in kv_layers],
@@ -65,14 +78,23 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
             if lm_ws is None:
                 lm_ws = torch.empty(lm_head_confidence_workspace_bytes(z.shape[0], z.shape[1], V), dtype=torch.uint8, device=dev)
             conf = lm_head_confidence(z, lm_head_weight, suffix_len, out=conf, workspace=lm_ws)
-        flip_update(conf[0], prefix_len, suffix_len, base, last_id, counters)
+        flip_update(conf[0], prefix_len, suffix_len, base, last_id, counters, window=flip_window,
+                    step_counts=step_counts)
         out = commit(conf[2], conf[0], bitmap, V, tau, window, min_commit, snap_enabled,
                      prefix_len, suffix_len, tokens=tokens, layers=table, C=tokens.shape[1], out=out,
                      **(commit_kw or {}))
 
     while True:
-        if steps % poll == 0 and int(suffix_len.max().item()) == 0:
-            break
+        if steps % poll == 0:
+            if out is None:
+                left, stalled = int(suffix_len.max().item()), 0
+            else:   # one transfer: positions left, and whether a sequence that has some committed nothing
+                left, stalled = torch.stack([suffix_len.max(), ((out["commit_len"] == 0) & (suffix_len > 0)).any().to(torch.int32)]).tolist()
+            if left == 0:
+                break
+            if stalled and min_commit >= 1:
+                raise LspError(f"decode_loop: a sequence with active positions committed nothing at step {steps - 1} "
+                               f"(status_flags {out['status_flags'].tolist()}): cache or token buffer full")
         if stop_after is not None and steps >= stop_after:
             break
         assert steps < max_steps
@@ -96,12 +118,17 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
             one_step(z)
         if timed:
             events[-1][1].record()
+        if step_counts is not None:
+            trace.append(step_counts.clone())
         if observer is not None:
             observer(steps, z, conf, out)
         steps += 1
     c = counters.tolist()
     committed = int((prefix_len - base).sum().item())
-    res = dict(steps=steps, flips=c[0], flip_denominator=c[1], committed=committed)
+    res = dict(steps=steps, flips=c[0], flip_denominator=c[1], window_flips=c[2], window_denominator=c[3],
+               committed=committed)
+    if flip_trace:
+        res["flip_trace"] = torch.stack(trace).cpu() if trace else torch.zeros((0, B, 2), dtype=torch.int32)
     if timed:
         torch.cuda.synchronize()
         res["lsp_ms_steps"] = [a.elapsed_time(b) for a, b in events]

@@ -133,14 +133,19 @@ def test_c2_full_size(lsp, oracle):
     print("c2 attention max abs err", err)
 
 
-def _sampled(lsp, oracle, w, n=96, seed=3, layer=0):
+def _sampled(lsp, oracle, w, n=96, seed=3, layer=0, heads=None, rows_per_head=0):
     kv = W.make_layer_kv(w, layer, device="cuda")
     pl, sl = W.make_lengths(w)
     out = lsp.attn_step(kv["q"], kv["k_suf"], kv["v_suf"], kv["k_cache"], kv["v_cache"], pl.cuda(), sl.cuda())
     torch.cuda.synchronize()
     g = torch.Generator().manual_seed(seed)
-    rows = torch.stack([torch.randint(0, w.B, (n,), generator=g), torch.randint(0, w.S, (n,), generator=g),
-                        torch.randint(0, w.Hq, (n,), generator=g)], dim=1).to(torch.int32)
+    if heads is None:
+        rows = torch.stack([torch.randint(0, w.B, (n,), generator=g), torch.randint(0, w.S, (n,), generator=g),
+                            torch.randint(0, w.Hq, (n,), generator=g)], dim=1).to(torch.int32)
+    else:   # the named heads of every sequence, seeded rows of each (first and last row among them)
+        rows = torch.tensor([[b, i, h] for b in range(w.B) for h in heads
+                             for i in [0, w.S - 1] + torch.randint(0, w.S, (rows_per_head - 2,), generator=g).tolist()],
+                            dtype=torch.int32)
     rows[0] = torch.tensor([0, 0, 0]); rows[1] = torch.tensor([w.B - 1, w.S - 1, w.Hq - 1])
     ref = oracle.attention(**{k: v.cpu() for k, v in kv.items()}, prefix_len=pl, suffix_len=sl, rows=rows)
     got = out[rows[:, 0].long().cuda(), rows[:, 1].long().cuda(), rows[:, 2].long().cuda()].float().cpu()
@@ -158,6 +163,13 @@ def test_c3_gqa_sampled(lsp, oracle):
 
 def test_c4_shape_one_layer_sampled(lsp, oracle):
     _sampled(lsp, oracle, W.C4, n=64, layer=5)
+
+
+@pytest.mark.parametrize("layer", [0, 15, 31])
+def test_c4_shape_first_middle_last_layer_heads_0_13_31(lsp, oracle, layer):
+    """Config 4's first, middle and last layer (their own seeded operands): heads 0, 13 and
+    31 of every sequence, 12 seeded query rows each, all 5120 keys, against the oracle."""
+    _sampled(lsp, oracle, W.C4, layer=layer, seed=40 + layer, heads=(0, 13, 31), rows_per_head=12)
 
 
 @pytest.mark.parametrize("D,Hq,Hkv,S", [(128, 16, 4, 600), (64, 16, 16, 520), (128, 72, 8, 100)])
