@@ -102,6 +102,25 @@ int32_t lsp_attn_step(const lsp_attn_desc *desc, const void *q, const void *k_su
                       const int32_t *prefix_len, const int32_t *suffix_len, void *out,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * lsp_attn_step for every layer of the denoiser call in ONE launch (Algorithm 1
+ * line 4 runs the attention once per layer inside each iteration of the line-3
+ * loop; late in the loop, when few positions are active, a launch per layer
+ * costs more than the work).  q_layers, k_suf_layers, v_suf_layers,
+ * k_cache_layers, v_cache_layers, out_layers: HOST arrays of num_layers DEVICE
+ * pointers (read during the call), each operand as for lsp_attn_step; all
+ * layers share the descriptor (shapes, strides) and the length arrays.  Layers
+ * are independent: out_layers[l] depends on layer l's operands only.  More than
+ * 32 layers are issued as several launches of 32; fp32 operands as one launch
+ * per layer.
+ */
+int32_t lsp_attn_step_layers(const lsp_attn_desc *desc, int32_t num_layers, const void *const *q_layers,
+                             const void *const *k_suf_layers, const void *const *v_suf_layers,
+                             const void *const *k_cache_layers, const void *const *v_cache_layers,
+                             const int32_t *prefix_len, const int32_t *suffix_len,
+                             void *const *out_layers, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
 /* ------------------------------------------------------------------------- *
  * Per-position confidence (Eq. 1; Algorithm 1 line 5).
  *
@@ -244,11 +263,14 @@ int32_t lsp_select_scattered(const float *margin, int32_t B, int32_t S, const in
 /*
  * Gathered append: for every layer, cache rows [P_b, P_b + k_b) receive the
  * suffix rows sel_index[b, 0..k_b) in that order (K and V), with k_b = count[b]
- * cut to the cache room C - P_b; then prefix_len[b] += k_b and appended[b] = k_b
- * (appended may be NULL).  suffix_len is not touched: after a scattered commit
+ * cut to the cache room C - P_b and to the length of the list, which ends at
+ * its first negative entry (lsp_select_scattered pads with -1 when fewer than
+ * count[b] positions are active: no more positions can be committed than
+ * exist); then appended[b] = k_b (device int32[B], required) and
+ * prefix_len[b] += k_b.  suffix_len is not touched: after a scattered commit
  * the remaining positions are no longer a suffix.  Layouts, alignment and the
  * HOST pointer tables as for lsp_commit; strides in elements, 0 = dense.
- * Indices outside [0,S) are clamped into the buffer.
+ * Indices above S-1 are clamped into the buffer.
  */
 int32_t lsp_kv_gather_append(int32_t kv_dtype, int32_t B, int32_t S, int32_t Hkv, int32_t D, int32_t C,
                              int32_t num_layers, int64_t suf_batch_stride, int64_t cache_batch_stride,

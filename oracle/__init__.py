@@ -30,6 +30,11 @@ def num_threads() -> int:
     return int(lib().oracle_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Threads for the oracle's OpenMP loops (the benchmark also times it on one thread)."""
+    lib().oracle_set_num_threads(int(n))
+
+
 def _dt(t: torch.Tensor) -> int:
     if t.dtype == torch.float32:
         return 0

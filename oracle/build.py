@@ -16,5 +16,18 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+def build_sanitized(out_dir: str) -> tuple[str, str]:
+    """The oracle's own driver (oracle/sanitize_driver.c, which includes lsp_oracle.c)
+    as two executables in out_dir: one plain, one under -fsanitize=address,undefined.
+    Returns (plain, sanitized)."""
+    drv = os.path.join(HERE, "sanitize_driver.c")
+    plain, san = os.path.join(out_dir, "oracle_driver"), os.path.join(out_dir, "oracle_driver_asan")
+    base = ["gcc", "-O1", "-g", "-std=c99", "-fopenmp", "-Wall", "-Wextra", "-I", HERE, drv, "-lm"]
+    subprocess.run(base + ["-o", plain], check=True)
+    subprocess.run(base + ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-o", san],
+                   check=True)
+    return plain, san
+
+
 if __name__ == "__main__":
     print(build())

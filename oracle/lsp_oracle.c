@@ -360,6 +360,10 @@ int oracle_gather_append(int kv_dtype, int B, int S, int Hkv, int D, int C, int 
         if (k < 0) k = 0;
         for (int j = 0; j < k; ++j) {
             int src = sel_index[(int64_t)b * S + j];
+            if (src < 0) { /* the list ends here: fewer positions were active than count[b] */
+                k = j;
+                break;
+            }
             for (int l = 0; l < layers; ++l) {
                 memcpy((char *)k_cache[l] + ((size_t)b * C + P + j) * row,
                        (const char *)k_suf[l] + ((size_t)b * S + src) * row, row);
@@ -423,6 +427,8 @@ int oracle_lm_head_confidence(int dtype, const void *hidden, const void *weight,
 #ifdef _OPENMP
 #include <omp.h>
 int oracle_num_threads(void) { return omp_get_max_threads(); }
+void oracle_set_num_threads(int n) { if (n > 0) omp_set_num_threads(n); }
 #else
 int oracle_num_threads(void) { return 1; }
+void oracle_set_num_threads(int n) { (void)n; }
 #endif

@@ -43,7 +43,7 @@ class CommitDesc(ctypes.Structure):
                 ("alpha", ctypes.c_float), ("beta", ctypes.c_float), ("max_commit", ctypes.c_int32)]
 
 
-EXPORTS = ["lsp_version", "lsp_last_error", "lsp_attn_workspace_bytes", "lsp_attn_step",
+EXPORTS = ["lsp_version", "lsp_last_error", "lsp_attn_workspace_bytes", "lsp_attn_step", "lsp_attn_step_layers",
            "lsp_confidence_workspace_bytes", "lsp_confidence", "lsp_confidence_static_scratch_bytes",
            "lsp_confidence_static", "lsp_commit_workspace_bytes",
            "lsp_commit", "lsp_flip_update", "lsp_select_scattered", "lsp_kv_gather_append",
@@ -63,7 +63,7 @@ def lib() -> ctypes.CDLL:
         for n in ("lsp_attn_workspace_bytes", "lsp_confidence_workspace_bytes", "lsp_commit_workspace_bytes",
                   "lsp_lm_head_confidence_workspace_bytes", "lsp_confidence_static_scratch_bytes"):
             getattr(L, n).restype = ctypes.c_size_t
-        for n in ("lsp_attn_step", "lsp_confidence", "lsp_confidence_static", "lsp_commit", "lsp_flip_update", "lsp_select_scattered",
+        for n in ("lsp_attn_step", "lsp_attn_step_layers", "lsp_confidence", "lsp_confidence_static", "lsp_commit", "lsp_flip_update", "lsp_select_scattered",
                   "lsp_kv_gather_append", "lsp_attn_step_gather", "lsp_lm_head_confidence"):
             getattr(L, n).restype = ctypes.c_int32
         _lib = L
@@ -145,6 +145,48 @@ def attn_step(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len, scale=0
                                         _stream())
     _check(rc, "lsp_attn_step")
     return out
+
+
+class AttnLayerTable:
+    """Host arrays of per-layer device pointers for lsp_attn_step_layers, built once and
+    reused (all layers must share shape, dtype and strides)."""
+
+    def __init__(self, q, k_suf, v_suf, k_cache, v_cache, out):
+        n = len(q)
+        assert len(k_suf) == len(v_suf) == len(k_cache) == len(v_cache) == len(out) == n > 0
+        for lst in (q, k_suf, v_suf, k_cache, v_cache, out):
+            for t in lst:
+                _dev(t)
+                assert t.shape == lst[0].shape and t.stride() == lst[0].stride() and t.dtype == q[0].dtype
+        assert v_suf[0].stride() == k_suf[0].stride() and v_cache[0].stride() == k_cache[0].stride()
+        Arr = ctypes.c_void_p * n
+        self.n = n
+        self.arrays = [Arr(*[t.data_ptr() for t in lst]) for lst in (q, k_suf, v_suf, k_cache, v_cache, out)]
+        self.keep = (q, k_suf, v_suf, k_cache, v_cache, out)
+        B, S, Hq, D = q[0].shape
+        self.desc = AttnDesc(dtype=_dtype(q[0]), B=B, S=S, Hq=Hq, Hkv=k_suf[0].shape[2], D=D, C=k_cache[0].shape[1])
+        self.desc.q_stride = _strides3(q[0])
+        self.desc.kv_suf_stride = _strides3(k_suf[0])
+        self.desc.cache_stride = _strides3(k_cache[0])
+        self.desc.o_stride = _strides3(out[0])
+        self.out = out
+
+
+def attn_step_layers(table: AttnLayerTable, prefix_len, suffix_len, scale=0.0, workspace=None):
+    """lsp_attn_step_layers: the attention of every layer of `table` in one launch.
+    Returns the list of per-layer outputs (table.out)."""
+    _dev(prefix_len, suffix_len)
+    table.desc.scale = float(scale)
+    need = lib().lsp_attn_workspace_bytes(ctypes.byref(table.desc))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=prefix_len.device)
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    a = table.arrays
+    rc = lib().lsp_attn_step_layers(ctypes.byref(table.desc), table.n, a[0], a[1], a[2], a[3], a[4],
+                                    _ptr(prefix_len), _ptr(suffix_len), a[5], _ptr(workspace),
+                                    ctypes.c_size_t(wb), _stream())
+    _check(rc, "lsp_attn_step_layers")
+    return table.out
 
 
 def confidence_workspace_bytes(B, S, V) -> int:

@@ -16,6 +16,27 @@ struct AttnArgs {
   const int32_t *cache_rows;  // gather form only: key t < P_b of sequence b is cache row cache_rows[b*C + t]; else null
 };
 
+// Operands of several layers for ONE launch (lsp_attn_step_layers): passed to the
+// kernels by value, the layer is the slow grid index.  n = 0: single-layer call,
+// the pointers in AttnArgs are used as they are.
+constexpr int kMaxAttnLayers = 32;
+struct AttnLayers {
+  int32_t n;
+  const void *q[kMaxAttnLayers], *k_suf[kMaxAttnLayers], *v_suf[kMaxAttnLayers];
+  const void *k_cache[kMaxAttnLayers], *v_cache[kMaxAttnLayers];
+  void *out[kMaxAttnLayers];
+};
+// This workgroup's layer (grid index y) replaces the operand pointers.
+__device__ __forceinline__ AttnArgs for_layer(const AttnArgs &in, const AttnLayers &L) {
+  AttnArgs a = in;
+  if (L.n > 0) {
+    const int l = blockIdx.y;
+    a.q = L.q[l]; a.k_suf = L.k_suf[l]; a.v_suf = L.v_suf[l];
+    a.k_cache = L.k_cache[l]; a.v_cache = L.v_cache[l]; a.out = L.out[l];
+  }
+  return a;
+}
+
 // Cache row that holds key t (t < P_b) of sequence b.
 template <bool GATHER>
 __device__ __forceinline__ int cache_row(const AttnArgs &a, int b, int t) {
@@ -25,7 +46,7 @@ __device__ __forceinline__ int cache_row(const AttnArgs &a, int b, int t) {
 }
 
 int32_t launch_attn_f32(const AttnArgs &a, hipStream_t st);
-int32_t launch_attn_bf16(const AttnArgs &a, hipStream_t st);
+int32_t launch_attn_bf16(const AttnArgs &a, const AttnLayers &layers, hipStream_t st);
 size_t attn_bf16_workspace_bytes(int32_t B, int32_t S, int32_t Hq, int32_t D);
 
 }  // namespace lsp

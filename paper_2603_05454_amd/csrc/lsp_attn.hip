@@ -77,10 +77,68 @@ int32_t attn_entry(const lsp_attn_desc *d, const void *q, const void *k_suf, con
   a.cache_rows = cache_rows;
   a.unit_group = 1;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  return d->dtype == LSP_F32 ? launch_attn_f32(a, st) : launch_attn_bf16(a, st);
+  AttnLayers none;
+  none.n = 0;
+  return d->dtype == LSP_F32 ? launch_attn_f32(a, st) : launch_attn_bf16(a, none, st);
 }
 }  // namespace
 }  // namespace lsp
+
+extern "C" int32_t lsp_attn_step_layers(const lsp_attn_desc *d, int32_t num_layers, const void *const *q_layers,
+                                        const void *const *k_suf_layers, const void *const *v_suf_layers,
+                                        const void *const *k_cache_layers, const void *const *v_cache_layers,
+                                        const int32_t *prefix_len, const int32_t *suffix_len,
+                                        void *const *out_layers, void *workspace, size_t workspace_bytes,
+                                        void *stream) {
+  using namespace lsp;
+  AttnArgs a;
+  const int32_t rc = check(d, a);
+  if (rc != LSP_OK) return rc;
+  LSP_CHECK_ARG(num_layers > 0, "lsp_attn_step_layers: num_layers must be positive");
+  LSP_CHECK_ARG(q_layers && k_suf_layers && v_suf_layers && k_cache_layers && v_cache_layers && out_layers &&
+                    prefix_len && suffix_len,
+                "lsp_attn_step_layers: null pointer");
+  for (int l = 0; l < num_layers; ++l) {
+    LSP_CHECK_ARG(q_layers[l] && k_suf_layers[l] && v_suf_layers[l] && k_cache_layers[l] && v_cache_layers[l] && out_layers[l],
+                  "lsp_attn_step_layers: null operand in layer %d", l);
+    LSP_CHECK_ARG(aligned16(q_layers[l]) && aligned16(k_suf_layers[l]) && aligned16(v_suf_layers[l]) &&
+                      aligned16(k_cache_layers[l]) && aligned16(v_cache_layers[l]) && aligned16(out_layers[l]),
+                  "lsp_attn_step_layers: operands of layer %d must be 16-byte aligned", l);
+  }
+  const size_t need = lsp_attn_workspace_bytes(d);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))) {
+    set_error("lsp_attn_step_layers: workspace of %zu bytes (256-byte aligned) required, got %zu", need, workspace_bytes);
+    return LSP_ERR_WORKSPACE;
+  }
+  a.prefix_len = prefix_len; a.suffix_len = suffix_len; a.workspace = workspace;
+  a.cache_rows = nullptr;
+  a.unit_group = 1;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int l0 = 0; l0 < num_layers; l0 += kMaxAttnLayers) {
+    const int nl = num_layers - l0 < kMaxAttnLayers ? num_layers - l0 : kMaxAttnLayers;
+    if (d->dtype == LSP_F32) {  // the fp32 kernel is a precision path: one launch per layer
+      for (int l = l0; l < l0 + nl; ++l) {
+        a.q = q_layers[l]; a.k_suf = k_suf_layers[l]; a.v_suf = v_suf_layers[l];
+        a.k_cache = k_cache_layers[l]; a.v_cache = v_cache_layers[l]; a.out = out_layers[l];
+        const int32_t r = launch_attn_f32(a, st);
+        if (r != LSP_OK) return r;
+      }
+      continue;
+    }
+    AttnLayers L;
+    L.n = nl;
+    for (int l = 0; l < kMaxAttnLayers; ++l) {
+      const int s = l < nl ? l0 + l : l0;  // unused slots repeat a valid layer
+      L.q[l] = q_layers[s]; L.k_suf[l] = k_suf_layers[s]; L.v_suf[l] = v_suf_layers[s];
+      L.k_cache[l] = k_cache_layers[s]; L.v_cache[l] = v_cache_layers[s]; L.out[l] = out_layers[s];
+    }
+    a.q = L.q[0]; a.k_suf = L.k_suf[0]; a.v_suf = L.v_suf[0];
+    a.k_cache = L.k_cache[0]; a.v_cache = L.v_cache[0]; a.out = L.out[0];
+    const int32_t r = launch_attn_bf16(a, L, st);
+    if (r != LSP_OK) return r;
+  }
+  return LSP_OK;
+}
 
 extern "C" int32_t lsp_attn_step(const lsp_attn_desc *d, const void *q, const void *k_suf,
                                  const void *v_suf, const void *k_cache, const void *v_cache,

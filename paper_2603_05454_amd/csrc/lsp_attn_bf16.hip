@@ -39,9 +39,6 @@
 //    eight-stage LDS ring, one barrier every four blocks; described where it is
 //    defined.
 #include "lsp_attn.h"
-#ifdef LSP_TUNE
-#include <stdlib.h>
-#endif
 
 namespace lsp {
 namespace {
@@ -235,9 +232,6 @@ inline int64_t place_grid(AttnArgs &a, int qtile) {
   const int64_t QT = (a.S + qtile - 1) / qtile;
   const int64_t units8 = (int64_t(a.B) * a.Hkv + 7) / 8;  // units per XCD
   int64_t G = units8 < kUnitGroup ? units8 : kUnitGroup;
-#ifdef LSP_TUNE
-  if (getenv("LSP_ATTN_G")) G = atoi(getenv("LSP_ATTN_G"));
-#endif
   a.unit_group = int32_t(G);
   const int64_t groups = (units8 + G - 1) / G;
   return groups * G * (a.Hq / a.Hkv) * QT * 8;
@@ -547,8 +541,9 @@ __device__ __forceinline__ void key_split_body(const AttnArgs &a, int b, int g, 
 }
 
 template <int D, int WM, int WK, bool GATHER>
-__global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a_in, AttnLayers layers) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const AttnArgs a = for_layer(a_in, layers);
   const Place pl = place(a, 32 * WM);
   if (!pl.valid) return;
   const int N = min(max(a.suffix_len[pl.b], 0), a.S);
@@ -558,23 +553,18 @@ __global__ __launch_bounds__(64 * WM * WK, 2) void attn_bf16_kernel(AttnArgs a) 
 }
 
 template <int D, int WM, int WK, bool GATHER>
-int32_t launch_g(AttnArgs a, hipStream_t st) {
+int32_t launch_g(AttnArgs a, const AttnLayers &layers, hipStream_t st) {
   const int64_t nwg = place_grid(a, 32 * WM);
   if (nwg > 0x7fffffff) {
     set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
     return LSP_ERR_UNSUPPORTED;
   }
-  const dim3 grid(static_cast<unsigned>(nwg), 1, 1);
+  const dim3 grid(static_cast<unsigned>(nwg), layers.n > 0 ? layers.n : 1, 1);
   const size_t lds = size_t(WM * WK) * Geo<D>::WAVE_LDS + size_t(WM) * 32 * Geo<D>::KPITCH;  // wave regions + Q rows
   auto kern = attn_bf16_kernel<D, WM, WK, GATHER>;
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
-    if (e != hipSuccess) return hip_fail(e, "lsp_attn_step: hipFuncSetAttribute");
-    configured = true;
-  }
-  kern<<<grid, 64 * WM * WK, lds, st>>>(a);
+  static std::atomic<uint64_t> configured{0};  // per instantiation, one bit per device
+  if (const int32_t rc = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, configured, "lsp_attn_step: hipFuncSetAttribute")) return rc;
+  kern<<<grid, 64 * WM * WK, lds, st>>>(a, layers);
   LSP_CHECK_LAUNCH("lsp_attn_step: bf16 launch");
   return LSP_OK;
 }
@@ -589,7 +579,8 @@ struct TileGeo {
 };
 
 template <int D, int WM, int OCC, int PD, bool GATHER>
-__global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a_in, AttnLayers layers) {
+  const AttnArgs a = for_layer(a_in, layers);
   using TG = TileGeo<D>;
   constexpr int NT = 64 * WM;
   constexpr int KK = D / 16;
@@ -757,7 +748,7 @@ __global__ __launch_bounds__(64 * WM, OCC) void attn_bf16_tile_kernel(AttnArgs a
 }
 
 template <int D, int WM, int OCC, int PD, bool GATHER>
-int32_t launch_tile_g(AttnArgs a, hipStream_t st) {
+int32_t launch_tile_g(AttnArgs a, const AttnLayers &layers, hipStream_t st) {
   const int64_t nwg = place_grid(a, 32 * WM);
   if (nwg > 0x7fffffff) {
     set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
@@ -765,14 +756,9 @@ int32_t launch_tile_g(AttnArgs a, hipStream_t st) {
   }
   const size_t lds = 2 * size_t(TileGeo<D>::STAGE);  // two shared stages
   auto kern = attn_bf16_tile_kernel<D, WM, OCC, PD, GATHER>;
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
-    if (e != hipSuccess) return hip_fail(e, "lsp_attn_step: hipFuncSetAttribute");
-    configured = true;
-  }
-  kern<<<dim3(static_cast<unsigned>(nwg), 1, 1), 64 * WM, lds, st>>>(a);
+  static std::atomic<uint64_t> configured{0};  // per instantiation, one bit per device
+  if (const int32_t rc = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, configured, "lsp_attn_step: hipFuncSetAttribute")) return rc;
+  kern<<<dim3(static_cast<unsigned>(nwg), layers.n > 0 ? layers.n : 1, 1), 64 * WM, lds, st>>>(a, layers);
   LSP_CHECK_LAUNCH("lsp_attn_step: bf16 tile launch");
   return LSP_OK;
 }
@@ -829,7 +815,8 @@ __device__ __forceinline__ void ring_issue(RingLoad L, int jb, unsigned char *kd
   load_to_lds(vp, vdst);
 }
 template <int NS, int BS, bool GATHER>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_ring_kernel(AttnArgs a) {
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_ring_kernel(AttnArgs a_in, AttnLayers layers) {
+  const AttnArgs a = for_layer(a_in, layers);
   constexpr int D = 128, WM = 8, KK = D / 16, DB = D / 32;
   constexpr int TILE = 32 * D * 2, VBASE = NS * TILE;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -997,7 +984,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 
 template <int NS, int BS, bool GATHER>
-int32_t launch_ring_g(AttnArgs a, hipStream_t st) {
+int32_t launch_ring_g(AttnArgs a, const AttnLayers &layers, hipStream_t st) {
   const int64_t nwg = place_grid(a, 256);
   if (nwg > 0x7fffffff) {
     set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
@@ -1008,52 +995,48 @@ int32_t launch_ring_g(AttnArgs a, hipStream_t st) {
   const size_t lds_split = 8 * size_t(Geo<128>::WAVE_LDS) + 32 * size_t(Geo<128>::KPITCH);
   const size_t lds = lds_ring > lds_split ? lds_ring : lds_split;
   auto kern = attn_bf16_ring_kernel<NS, BS, GATHER>;
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
-    if (e != hipSuccess) return hip_fail(e, "lsp_attn_step: hipFuncSetAttribute");
-    configured = true;
-  }
-  kern<<<dim3(static_cast<unsigned>(nwg), 1, 1), 512, lds, st>>>(a);
+  static std::atomic<uint64_t> configured{0};  // per instantiation, one bit per device
+  if (const int32_t rc = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, configured, "lsp_attn_step: hipFuncSetAttribute")) return rc;
+  kern<<<dim3(static_cast<unsigned>(nwg), layers.n > 0 ? layers.n : 1, 1), 512, lds, st>>>(a, layers);
   LSP_CHECK_LAUNCH("lsp_attn_step: bf16 ring launch");
   return LSP_OK;
 }
 
 // contiguous cache, or rows through an index (Scattered-Margin measurement)
 template <int D, int WM, int WK>
-int32_t launch(const AttnArgs &a, hipStream_t st) {
-  return a.cache_rows ? launch_g<D, WM, WK, true>(a, st) : launch_g<D, WM, WK, false>(a, st);
+int32_t launch(const AttnArgs &a, const AttnLayers &layers, hipStream_t st) {
+  return a.cache_rows ? launch_g<D, WM, WK, true>(a, layers, st) : launch_g<D, WM, WK, false>(a, layers, st);
 }
 template <int D, int WM, int OCC, int PD>
-int32_t launch_tile(const AttnArgs &a, hipStream_t st) {
-  return a.cache_rows ? launch_tile_g<D, WM, OCC, PD, true>(a, st) : launch_tile_g<D, WM, OCC, PD, false>(a, st);
+int32_t launch_tile(const AttnArgs &a, const AttnLayers &layers, hipStream_t st) {
+  return a.cache_rows ? launch_tile_g<D, WM, OCC, PD, true>(a, layers, st) : launch_tile_g<D, WM, OCC, PD, false>(a, layers, st);
 }
 
 template <int D>
-int32_t dispatch(const AttnArgs &a, hipStream_t st) {
+int32_t dispatch(const AttnArgs &a, const AttnLayers &layers, hipStream_t st) {
   // Enough (sequence, head, row) triples to give every compute unit several
   // query tiles: the shared-tile kernel, with the widest tile the suffix fills.
   // Otherwise the wave-private kernel with the key range split between waves.
-  const int64_t rows = int64_t(a.B) * a.Hq * a.S;  // upper bound on (b,h,row) triples
+  // upper bound on (b,h,row) triples of the launch
+  const int64_t rows = int64_t(a.B) * a.Hq * a.S * (layers.n > 0 ? layers.n : 1);
   if (rows / 128 >= 256) {
     if constexpr (D == 128) {
-      if (a.S > 128) return a.cache_rows ? launch_ring_g<8, 4, true>(a, st) : launch_ring_g<8, 4, false>(a, st);
+      if (a.S > 128) return a.cache_rows ? launch_ring_g<8, 4, true>(a, layers, st) : launch_ring_g<8, 4, false>(a, layers, st);
     }
-    return launch_tile<D, 4, 2, 4>(a, st);
+    return launch_tile<D, 4, 2, 4>(a, layers, st);
   }
-  if (rows / 64 >= 512) return launch<D, 2, 2>(a, st);
-  if (rows / 32 >= 512) return launch<D, 1, 4>(a, st);
-  return launch<D, 1, 8>(a, st);
+  if (rows / 64 >= 512) return launch<D, 2, 2>(a, layers, st);
+  if (rows / 32 >= 512) return launch<D, 1, 4>(a, layers, st);
+  return launch<D, 1, 8>(a, layers, st);
 }
 
 }  // namespace
 
 size_t attn_bf16_workspace_bytes(int32_t, int32_t, int32_t, int32_t) { return 0; }
 
-int32_t launch_attn_bf16(const AttnArgs &a, hipStream_t st) {
-  if (a.D == 128) return dispatch<128>(a, st);
-  if (a.D == 64) return dispatch<64>(a, st);
+int32_t launch_attn_bf16(const AttnArgs &a, const AttnLayers &layers, hipStream_t st) {
+  if (a.D == 128) return dispatch<128>(a, layers, st);
+  if (a.D == 64) return dispatch<64>(a, layers, st);
   set_error("lsp_attn_step: bf16 head_dim %d not built (64, 128)", a.D);
   return LSP_ERR_UNSUPPORTED;
 }

@@ -1,6 +1,8 @@
 // Internal helpers of liblsp (HIP side only).
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stdint.h>
 #include <stdio.h>
 
@@ -29,6 +31,22 @@ inline int32_t hip_fail(hipError_t e, const char *what) {
     hipError_t e__ = hipGetLastError();                 \
     if (e__ != hipSuccess) return lsp::hip_fail(e__, what); \
   } while (0)
+
+// Raise a kernel's dynamic LDS limit.  The attribute belongs to (kernel, device),
+// so `done` keeps one bit per device ordinal (one atomic per kernel instantiation):
+// the first launch on each GPU sets it, from whichever host thread gets there
+// (two threads racing both set the same value, which is harmless).
+inline int32_t ensure_dynamic_lds(const void *kernel, size_t bytes, std::atomic<uint64_t> &done, const char *what) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, what);
+  const uint64_t bit = dev >= 0 && dev < 64 ? uint64_t(1) << dev : 0;  // ordinals beyond 63: set every time
+  if (bit != 0 && (done.load(std::memory_order_acquire) & bit)) return LSP_OK;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, int(bytes));
+  if (e != hipSuccess) return hip_fail(e, what);
+  done.fetch_or(bit, std::memory_order_release);
+  return LSP_OK;
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t elem_size(int32_t dtype) { return dtype == LSP_F32 ? 4 : 2; }

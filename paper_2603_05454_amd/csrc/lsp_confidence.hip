@@ -32,9 +32,6 @@
 #include <type_traits>
 
 #include "lsp_common.h"
-#ifdef LSP_TUNE
-#include <stdlib.h>
-#endif
 
 namespace lsp {
 namespace {
@@ -390,9 +387,6 @@ inline Plan plan(int64_t rows, int V, int elem_bytes) {
   const int64_t nvec = int64_t(V) * elem_bytes / 16;
   while (nt < 512 && nvec / nt >= 96) nt *= 2;
   while (nt < 512 && rows * (nt / 64) < 2048) nt *= 2;
-#ifdef LSP_TUNE
-  if (getenv("LSP_CONF_NT")) nt = atoi(getenv("LSP_CONF_NT"));
-#endif
   int splits = 1;
   const int64_t waves = rows * (nt / 64);
   if (waves < 1024) {

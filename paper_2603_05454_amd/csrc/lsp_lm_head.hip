@@ -26,9 +26,6 @@
 // RB row tiles: each weight slice is then read by RB and each hidden slice by
 // VB workgroups out of the same L2.
 #include <float.h>
-#ifdef LSP_TUNE
-#include <stdlib.h>
-#endif
 
 #include "lsp_common.h"
 
@@ -352,24 +349,14 @@ template <int WV, int WR>
 int32_t launch_lm_head_t(const LmArgs &a, int64_t nwg, hipStream_t st) {
   const size_t lds = 2 * size_t(STAGE);  // two K steps in LDS
   auto kern = lm_head_kernel<WV, WR>;
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
-    if (e != hipSuccess) return hip_fail(e, "lsp_lm_head_confidence: hipFuncSetAttribute");
-    configured = true;
-  }
+  static std::atomic<uint64_t> configured{0};  // per instantiation, one bit per device
+  if (const int32_t rc = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, configured, "lsp_lm_head_confidence: hipFuncSetAttribute")) return rc;
   kern<<<dim3(static_cast<unsigned>(nwg)), 64 * WV * WR, lds, st>>>(a);
   LSP_CHECK_LAUNCH("lsp_lm_head_confidence: launch");
   return LSP_OK;
 }
 
 int32_t launch_lm_head(const LmArgs &a, int64_t nwg, hipStream_t st) {
-#ifdef LSP_TUNE
-  const char *v = getenv("LSP_LM_VARIANT");
-  if (v && atoi(v) == 1) return launch_lm_head_t<2, 4>(a, nwg, st);
-  if (v && atoi(v) == 2) return launch_lm_head_t<2, 2>(a, nwg, st);
-#endif
   // Four waves of 128 x 128 outputs each need the fewest LDS reads per matrix
   // instruction (8 fragment reads feed 16 instructions; eight waves of 128 x 64
   // need 6 for 8) and win once several row tiles share every weight tile.  With

@@ -99,17 +99,38 @@ struct LayerPtrs {
 
 constexpr int kRowThreads = 256;
 
-// grid: (S candidate rows, B, 2 * layers in this launch); row j of sequence b is
-// live when j < min(count[b], C - P_b).  One workgroup copies one K or V row.
-__global__ __launch_bounds__(kRowThreads) void gather_append_kernel(
-    LayerPtrs ptrs, int S, int C, int64_t row_bytes, int64_t suf_batch_bytes,
-    int64_t cache_batch_bytes, const int32_t *__restrict__ sel_index,
-    const int32_t *__restrict__ count, const int32_t *__restrict__ prefix_len) {
-  const int j = blockIdx.x, b = blockIdx.y;
+// Rows to append per sequence: count[b], cut to the cache room and to the length
+// of the list (it ends at its first negative entry: lsp_select_scattered pads
+// with -1 when fewer positions than count[b] are active).  One workgroup per
+// sequence.
+__global__ __launch_bounds__(256) void gather_count_kernel(int S, int C, const int32_t *__restrict__ sel_index,
+                                                           const int32_t *__restrict__ count,
+                                                           const int32_t *__restrict__ prefix_len,
+                                                           int32_t *__restrict__ appended) {
+  __shared__ int first_bad;
+  const int b = blockIdx.x;
   const int P = max(prefix_len[b], 0);
-  const int k = min(max(count[b], 0), max(C - P, 0));
-  if (j >= k) return;
-  const int src_row = min(max(sel_index[int64_t(b) * S + j], 0), S - 1);  // a bad index must not leave the buffer
+  const int k = min(min(max(count[b], 0), max(C - P, 0)), S);
+  if (threadIdx.x == 0) first_bad = k;
+  __syncthreads();
+  int mine = k;
+  for (int j = threadIdx.x; j < k; j += blockDim.x)
+    if (sel_index[int64_t(b) * S + j] < 0) mine = min(mine, j);
+  if (mine < k) atomicMin(&first_bad, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) appended[b] = first_bad;
+}
+
+// grid: (S candidate rows, B, 2 * layers in this launch); row j of sequence b is
+// live when j < appended[b].  One workgroup copies one K or V row.
+__global__ __launch_bounds__(kRowThreads) void gather_append_kernel(
+    LayerPtrs ptrs, int S, int64_t row_bytes, int64_t suf_batch_bytes,
+    int64_t cache_batch_bytes, const int32_t *__restrict__ sel_index,
+    const int32_t *__restrict__ appended, const int32_t *__restrict__ prefix_len) {
+  const int j = blockIdx.x, b = blockIdx.y;
+  if (j >= appended[b]) return;
+  const int P = max(prefix_len[b], 0);
+  const int src_row = min(sel_index[int64_t(b) * S + j], S - 1);  // a bad index must not leave the buffer (>= 0 here)
   const char *src = ptrs.src[blockIdx.z] + int64_t(b) * suf_batch_bytes + int64_t(src_row) * row_bytes;
   char *dst = ptrs.dst[blockIdx.z] + int64_t(b) * cache_batch_bytes + int64_t(P + j) * row_bytes;
   for (int64_t o = int64_t(threadIdx.x) * 16; o < row_bytes; o += int64_t(kRowThreads) * 16) {
@@ -118,14 +139,10 @@ __global__ __launch_bounds__(kRowThreads) void gather_append_kernel(
   }
 }
 
-__global__ void advance_prefix_kernel(int B, int C, const int32_t *__restrict__ count,
-                                      int32_t *__restrict__ prefix_len, int32_t *__restrict__ appended) {
+__global__ void advance_prefix_kernel(int B, const int32_t *__restrict__ appended, int32_t *__restrict__ prefix_len) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
-  const int P = max(prefix_len[b], 0);
-  const int k = min(max(count[b], 0), max(C - P, 0));
-  prefix_len[b] = P + k;
-  if (appended != nullptr) appended[b] = k;
+  prefix_len[b] = max(prefix_len[b], 0) + appended[b];
 }
 
 }  // namespace
@@ -159,7 +176,7 @@ extern "C" int32_t lsp_kv_gather_append(int32_t kv_dtype, int32_t B, int32_t S, 
                                         void *const *v_cache_layers, int32_t *prefix_len,
                                         int32_t *appended, void *stream) {
   using namespace lsp;
-  LSP_CHECK_ARG(sel_index && count && prefix_len, "lsp_kv_gather_append: null pointer");
+  LSP_CHECK_ARG(sel_index && count && prefix_len && appended, "lsp_kv_gather_append: null pointer");
   LSP_CHECK_ARG(kv_dtype == LSP_F32 || kv_dtype == LSP_BF16, "lsp_kv_gather_append: unknown kv_dtype");
   LSP_CHECK_ARG(B > 0 && B <= 65535 && S > 0 && Hkv > 0 && D > 0 && C > 0 && num_layers > 0,
                 "lsp_kv_gather_append: bad dimension");
@@ -181,6 +198,8 @@ extern "C" int32_t lsp_kv_gather_append(int32_t kv_dtype, int32_t B, int32_t S, 
                   "lsp_kv_gather_append: K/V pointer of layer %d is not 16-byte aligned", l);
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
+  gather_count_kernel<<<B, 256, 0, st>>>(S, C, sel_index, count, prefix_len, appended);
+  LSP_CHECK_LAUNCH("lsp_kv_gather_append: count launch");
   for (int l0 = 0; l0 < num_layers; l0 += kMaxLayersPerLaunch) {
     const int nl = num_layers - l0 < kMaxLayersPerLaunch ? num_layers - l0 : kMaxLayersPerLaunch;
     LayerPtrs p;
@@ -194,11 +213,11 @@ extern "C" int32_t lsp_kv_gather_append(int32_t kv_dtype, int32_t B, int32_t S, 
       p.src[l] = nullptr;
       p.dst[l] = nullptr;
     }
-    gather_append_kernel<<<dim3(S, B, 2 * nl), kRowThreads, 0, st>>>(p, S, C, row_bytes, suf_bb, cache_bb,
-                                                                     sel_index, count, prefix_len);
+    gather_append_kernel<<<dim3(S, B, 2 * nl), kRowThreads, 0, st>>>(p, S, row_bytes, suf_bb, cache_bb,
+                                                                     sel_index, appended, prefix_len);
     LSP_CHECK_LAUNCH("lsp_kv_gather_append: copy launch");
   }
-  advance_prefix_kernel<<<(B + 255) / 256, 256, 0, st>>>(B, C, count, prefix_len, appended);
+  advance_prefix_kernel<<<(B + 255) / 256, 256, 0, st>>>(B, appended, prefix_len);
   LSP_CHECK_LAUNCH("lsp_kv_gather_append: prefix launch");
   return LSP_OK;
 }

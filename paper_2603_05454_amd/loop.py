@@ -10,7 +10,7 @@ from __future__ import annotations
 
 import torch
 
-from . import (LayerTable, LspError, attn_step, commit, confidence, flip_update, lm_head_confidence,
+from . import (AttnLayerTable, LayerTable, LspError, attn_step_layers, commit, confidence, flip_update, lm_head_confidence,
                lm_head_confidence_workspace_bytes)
 
 
@@ -69,9 +69,10 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     def one_step(z):
         nonlocal out, conf, attn_out, lm_ws
         if run_attention and kv_layers is not None:
-            for L in kv_layers:
-                attn_out = attn_step(L["q"], L["k_suf"], L["v_suf"], L["k_cache"], L["v_cache"],
-                                     prefix_len, suffix_len, out=attn_out)
+            if attn_out is None:     # one output per layer (a denoiser consumes each of them), allocated once
+                attn_out = AttnLayerTable(*[[L[k] for L in kv_layers] for k in ("q", "k_suf", "v_suf", "k_cache", "v_cache")],
+                                          [torch.empty_like(L["q"]) for L in kv_layers])
+            attn_step_layers(attn_out, prefix_len, suffix_len)     # every layer in one launch
         if lm_head_weight is None:
             conf = confidence(z, suffix_len, out=conf)
         else:

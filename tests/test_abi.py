@@ -60,8 +60,17 @@ def test_argument_errors_are_reported_before_any_launch():
     # Scattered-Margin entry points
     assert L.lsp_select_scattered(None, 1, 4, None, None, None, None, None) == -1
     assert L.lsp_select_scattered(p, 1, 100000, p, p, p, p, None) == -2 and b"exceeds" in L.lsp_last_error()
-    assert L.lsp_kv_gather_append(1, 1, 4, 1, 3, 8, 1, ctypes.c_int64(0), ctypes.c_int64(0), p, p, p, p, p, p, p, None, None) == -1
+    assert L.lsp_kv_gather_append(1, 1, 4, 1, 3, 8, 1, ctypes.c_int64(0), ctypes.c_int64(0), p, p, p, p, p, p, p, p, None) == -1
     assert b"multiple of 16" in L.lsp_last_error()
+    assert L.lsp_kv_gather_append(1, 1, 4, 1, 8, 8, 1, ctypes.c_int64(0), ctypes.c_int64(0), p, p, p, p, p, p, p, None, None) == -1
+    assert b"null pointer" in L.lsp_last_error()        # appended is a required output
+    # the multi-layer attention call
+    d = lsp.AttnDesc(dtype=1, B=1, S=4, Hq=2, Hkv=2, D=128, C=8)
+    assert L.lsp_attn_step_layers(ctypes.byref(d), 0, p, p, p, p, p, p, p, p, None, ctypes.c_size_t(0), None) == -1
+    assert b"num_layers" in L.lsp_last_error()
+    tbl = (ctypes.c_void_p * 2)(ctypes.addressof(buf), 0)
+    assert L.lsp_attn_step_layers(ctypes.byref(d), 2, tbl, tbl, tbl, tbl, tbl, p, p, tbl, None, ctypes.c_size_t(0), None) == -1
+    assert b"layer 1" in L.lsp_last_error()
     d = lsp.AttnDesc(dtype=1, B=1, S=4, Hq=2, Hkv=2, D=128, C=8)
     rc = L.lsp_attn_step_gather(ctypes.byref(d), p, p, p, p, p, None, p, p, p, None, ctypes.c_size_t(0), None)
     assert rc == -1 and b"row index" in L.lsp_last_error()

@@ -283,3 +283,42 @@ def test_strided_views_many_rows_sampled(lsp, oracle):
     got = out[rows[:, 0].long().cuda(), rows[:, 1].long().cuda(), rows[:, 2].long().cuda()].float().cpu()
     assert (got - ref).abs().max().item() <= 2e-2
     assert torch.all(out[1, 407:].float() == 123.0)
+
+
+@pytest.mark.parametrize("cfg", ["f32_small", "bf16_short", "bf16_long_ragged", "bf16_d64"])
+def test_all_layers_in_one_launch(lsp, oracle, cfg):
+    """lsp_attn_step_layers over 3-5 layers with their own operands: every layer's output
+    against the oracle, and bit-identical to lsp_attn_step called layer by layer wherever
+    both take the same launch shape (one launch for all layers may pick a wider tile)."""
+    w, pl, sl, nl = {
+        "f32_small": (W.scaled(W.C1, B=2, S=40, P=30, C=64), torch.tensor([30, 7]), torch.tensor([40, 13]), 3),
+        "bf16_short": (W.scaled(W.C2, B=2, S=96, P=100, C=128, Hq=4, Hkv=2), torch.tensor([100, 0]), torch.tensor([96, 33]), 4),
+        "bf16_long_ragged": (W.scaled(W.C2, B=5, S=600, P=300, C=384, Hq=16, Hkv=4),
+                             torch.tensor([300, 0, 77, 131, 384]), torch.tensor([600, 529, 0, 1, 257]), 3),
+        "bf16_d64": (W.scaled(W.C2, B=3, S=520, P=64, C=128, Hq=16, Hkv=16, D=64), torch.tensor([64, 1, 128]), torch.tensor([520, 64, 300]), 5),
+    }[cfg]
+    pl, sl = pl.to(torch.int32), sl.to(torch.int32)
+    host = [W.make_layer_kv(w, l, prefix_len=pl) for l in range(nl)]
+    dev = [{k: v.cuda() for k, v in L.items()} for L in host]
+    outs = [torch.full(L["q"].shape, 123.0, dtype=L["q"].dtype, device="cuda") for L in dev]
+    table = lsp.AttnLayerTable(*[[L[k] for L in dev] for k in ("q", "k_suf", "v_suf", "k_cache", "v_cache")], outs)
+    lsp.attn_step_layers(table, pl.cuda(), sl.cuda())
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(3)
+    for l, (L, o) in enumerate(zip(host, outs)):
+        got = o.float().cpu()
+        if w.B * w.S * w.Hq <= 40000:
+            ref = oracle.attention(**L, prefix_len=pl, suffix_len=sl)
+            act = ~torch.isnan(ref)
+            assert (got[act] - ref[act]).abs().max().item() <= TOL[w.dtype], l
+            assert torch.all(got[~act] == 123.0)
+        else:
+            rows = torch.tensor([[b, i, int(torch.randint(0, w.Hq, (1,), generator=g))] for b in range(w.B)
+                                 for i in ([0, int(sl[b]) - 1] + torch.randint(0, max(int(sl[b]), 1), (14,), generator=g).tolist())
+                                 if int(sl[b]) > 0], dtype=torch.int32)
+            ref = oracle.attention(**L, prefix_len=pl, suffix_len=sl, rows=rows)
+            assert (got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()] - ref).abs().max().item() <= TOL[w.dtype], l
+            for b in range(w.B):
+                assert torch.all(got[b, int(sl[b]):] == 123.0)
+        single = _run(lsp, L, pl, sl)
+        assert (single - got).abs().max().item() <= 2 * TOL[w.dtype]      # both are within TOL of the oracle

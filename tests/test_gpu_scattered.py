@@ -108,3 +108,31 @@ def test_attention_over_index_addressed_cache(lsp, oracle, cfg):
     got = out[pick[:, 0].cuda(), pick[:, 1].cuda(), pick[:, 2].cuda()].float().cpu()
     tol = 1e-5 if w.dtype == "f32" else 2e-2
     assert (got - ref).abs().max().item() <= tol
+
+
+def test_gather_append_with_count_above_the_active_positions(lsp, oracle):
+    """count[b] > N_b: the selection is padded with -1 and the append stops at the padding
+    on both sides (rows appended = N_b, nothing written beyond them)."""
+    w = W.scaled(W.C1, B=4, S=300, P=10, C=400, Hq=2, Hkv=2, D=64, V=64, layers=2, dtype="bf16")
+    pl = torch.tensor([10, 0, 395, 20], dtype=torch.int32)        # sequence 2: room for 5 rows only
+    sl = torch.tensor([300, 7, 40, 0], dtype=torch.int32)
+    ct = torch.tensor([290, 300, 30, 12], dtype=torch.int32)      # 1 and 3 ask for more than they have
+    layers = [W.make_layer_kv(w, l, prefix_len=pl) for l in range(2)]
+    margin = torch.rand((4, 300), generator=torch.Generator().manual_seed(6))
+    ref = [{k: v.clone() for k, v in L.items()} for L in layers]
+    pl_r = pl.clone()
+    idx_r, _ = oracle.select_scattered(margin, sl, ct)
+    oracle.gather_append(idx_r, ct, pl_r, [L["k_suf"] for L in ref], [L["v_suf"] for L in ref],
+                         [L["k_cache"] for L in ref], [L["v_cache"] for L in ref])
+    assert (pl_r - pl).tolist() == [290, 7, 5, 0]
+    dev = [{k: v.cuda() for k, v in L.items()} for L in layers]
+    table = lsp.LayerTable([L["k_suf"] for L in dev], [L["v_suf"] for L in dev], [L["k_cache"] for L in dev], [L["v_cache"] for L in dev])
+    pl_g = pl.cuda()
+    idx_g, _ = lsp.select_scattered(margin.cuda(), sl.cuda(), ct.cuda())
+    assert torch.equal(idx_g.cpu(), idx_r)
+    app = lsp.kv_gather_append(idx_g, ct.cuda(), pl_g, table)
+    torch.cuda.synchronize()
+    assert torch.equal(pl_g.cpu(), pl_r) and app.cpu().tolist() == (pl_r - pl).tolist()
+    for Lg, Lr in zip(dev, ref):
+        for name in ("k_cache", "v_cache"):
+            assert torch.equal(Lg[name].cpu().view(torch.int16), Lr[name].view(torch.int16)), name

@@ -76,3 +76,27 @@ def test_gather_append_against_tensor_indexing(oracle):
                 assert torch.equal(L[name][b, 5:5 + k], L0[suf][b][rows])               # gathered rows, in order
                 assert torch.equal(L[name][b, :5], L0[name][b, :5])                     # prefix untouched
                 assert torch.equal(L[name][b, 5 + k:], L0[name][b, 5 + k:])             # rest untouched (poison)
+
+
+def test_gather_append_stops_where_the_selection_list_ends(oracle):
+    """count[b] larger than the number of active positions: the selection holds N_b entries
+    and is padded with -1; only those N_b rows are appended and the prefix advances by N_b
+    (no more positions can be committed than exist)."""
+    w = W.scaled(W.C1, B=3, S=12, P=3, C=40, Hq=2, Hkv=2, D=8, V=64, layers=2, dtype="f32")
+    layers = [W.make_layer_kv(w, l) for l in range(2)]
+    before = [{k: v.clone() for k, v in L.items()} for L in layers]
+    margin = torch.rand((3, 12), generator=torch.Generator().manual_seed(8))
+    sl = torch.tensor([12, 4, 0], dtype=torch.int32)
+    ct = torch.tensor([5, 9, 3], dtype=torch.int32)               # sequences 1 and 2 ask for more than they have
+    pl = torch.tensor([3, 3, 3], dtype=torch.int32)
+    idx, _ = oracle.select_scattered(margin, sl, ct)
+    assert (idx[1] >= 0).sum() == 4 and (idx[2] >= 0).sum() == 0
+    oracle.gather_append(idx, ct, pl, [L["k_suf"] for L in layers], [L["v_suf"] for L in layers],
+                         [L["k_cache"] for L in layers], [L["v_cache"] for L in layers])
+    assert pl.tolist() == [3 + 5, 3 + 4, 3]
+    for L, L0 in zip(layers, before):
+        for b, k in enumerate([5, 4, 0]):
+            rows = idx[b, :k].long()
+            assert torch.equal(L["k_cache"][b, 3:3 + k], L0["k_suf"][b][rows])
+            assert torch.equal(L["v_cache"][b, 3:3 + k], L0["v_suf"][b][rows])
+            assert torch.equal(L["k_cache"][b, 3 + k:], L0["k_cache"][b, 3 + k:])       # nothing beyond
