@@ -1002,6 +1002,172 @@ int32_t launch_ring_g(AttnArgs a, const AttnLayers &layers, hipStream_t st) {
   return LSP_OK;
 }
 
+// ---- long-suffix kernel, head_dim 128, contiguous cache: hand-scheduled block loop ----
+// Same tile (256 queries, 8 waves of 32, two waves per SIMD), same LDS ring and the
+// same arithmetic as attn_bf16_ring_kernel; what differs is who fixes the issue
+// order.  The block loop is one generated inline-asm statement (gen_attn_pipe.py
+// describes its pipeline, register map and synchronisation): a one-block software
+// pipeline per wave in which the soft-max of block j is issued between the matrix
+// instructions of S(j+1) = K(j+1).Q^T, every LDS fragment is requested half a block
+// before it is used, and no instruction waits on the one before it.
+// The loop only handles full 32-row blocks that lie wholly in the cache or wholly in
+// the suffix.  The ragged ends (the last P % 32 cache rows, the last N % 32 suffix
+// rows: at most two blocks per tile) are done first, by compiler-scheduled code with
+// the same fragment layout, on the same running (m, l, O) state.
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_pipe_kernel(AttnArgs a_in,
+                                                                                                       AttnLayers layers) {
+  const AttnArgs a = for_layer(a_in, layers);
+  constexpr int D = 128, WM = 8, KK = D / 16, DB = D / 32, NS = 8;
+  constexpr int TILE = 32 * D * 2, VBASE = NS * TILE;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  const Place pl = place(a, 32 * WM);
+  if (!pl.valid) return;
+  const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
+  const int N = min(max(a.suffix_len[b], 0), a.S);
+  const int P = min(max(a.prefix_len[b], 0), a.C);
+  {  // sequences down to a few active rows: key-split mode, as in attn_bf16_ring_kernel
+    const int tile = q0 / (32 * WM), QT = (a.S + 32 * WM - 1) / (32 * WM);
+    const int short_rows = 32 * min(QT, kShortSuffix / 32);
+    if (N <= short_rows) {
+      if (32 * tile < N) key_split_body<D, 1, WM, false>(a, b, g, h, 32 * tile, N, P, smem);
+      return;
+    }
+  }
+  if (q0 >= N) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int lq = lane & 31, hf = lane >> 5;
+
+  const int qi = q0 + wave * 32 + lq;
+  const uint16_t *qp = static_cast<const uint16_t *>(a.q) + b * a.qs[0] + int64_t(min(qi, N - 1)) * a.qs[1] + h * a.qs[2];
+  bf16x8 qf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8 *>(qp + 16 * kk + 8 * hf);
+
+  const char *kc = reinterpret_cast<const char *>(static_cast<const uint16_t *>(a.k_cache) + b * a.cs[0] + g * a.cs[2]);
+  const char *vc = reinterpret_cast<const char *>(static_cast<const uint16_t *>(a.v_cache) + b * a.cs[0] + g * a.cs[2]);
+  const char *ks = reinterpret_cast<const char *>(static_cast<const uint16_t *>(a.k_suf) + b * a.ks[0] + g * a.ks[2]);
+  const char *vs = reinterpret_cast<const char *>(static_cast<const uint16_t *>(a.v_suf) + b * a.ks[0] + g * a.ks[2]);
+  const int64_t cpitch = a.cs[1] * 2, spitch = a.ks[1] * 2;
+  // loader: this lane owns row lr of every block and 16-byte position pp of it
+  const int pp = lane & 15, lr = 4 * wave + (lane >> 4);
+  const int kcol = 16 * (pp ^ (lr & 15)), vcol = 64 * ((pp >> 2) ^ (lr & 3)) + 16 * (pp & 3);
+
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float mref = -INFINITY, lsum = 0.f;
+  const float sc = a.scale * kLog2e;
+
+  // fragment addresses inside stage 0 (as in attn_bf16_ring_kernel)
+  const unsigned char *kaddr[KK], *vaddr[DB];
+  {
+    const int y16 = 16 * (hf ^ (lq & 15));
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kaddr[kk] = smem + lq * (D * 2) + ((32 * kk) ^ y16);
+    const int s16 = lane & 15, r3 = (s16 >> 2) & 3;
+    const unsigned char *vbase = smem + VBASE + (4 * hf + (s16 >> 2)) * (D * 2) + (16 * ((lane >> 4) & 1) + 4 * (s16 & 3)) * 2;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) vaddr[db] = vbase + 64 * (db ^ r3);
+  }
+
+  // ---- ragged ends: rows [32*nc, P) of the cache and rows [32*ns, N) of the suffix ----
+  const int nc = P >> 5, ns = N >> 5;
+  auto ragged_block = [&](const char *kbase, const char *vbase, int64_t pitch, int cnt) {
+    // this lane's row, clamped into the block; rows >= cnt are masked below and their V slots zeroed
+    const int64_t off = int64_t(min(lr, cnt - 1)) * pitch;
+    load_to_lds(kbase + off + kcol, smem + 1024 * wave_s);
+    load_to_lds(vbase + off + vcol, smem + VBASE + 1024 * wave_s);
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    if (lr >= cnt) *reinterpret_cast<u32x4 *>(smem + VBASE + 1024 * wave + 16 * lane) = u32x4{0, 0, 0, 0};
+    __syncthreads();
+    bf16x8 kf[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kf[kk] = *reinterpret_cast<const bf16x8 *>(kaddr[kk]);
+    f32x16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
+    bf16x8 vf[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2) vf[db][k2] = vt_read<D * 2>(vaddr[db] + (16 * k2) * (D * 2));
+    softmax_pv<D>(s, oacc, mref, lsum, 0, cnt, sc, lane, vf);
+    __syncthreads();  // stage 0 is free again
+  };
+  if (P & 31) ragged_block(kc + int64_t(32 * nc) * cpitch, vc + int64_t(32 * nc) * cpitch, cpitch, P & 31);
+  if (N & 31) ragged_block(ks + int64_t(32 * ns) * spitch, vs + int64_t(32 * ns) * spitch, spitch, N & 31);
+
+  // ---- the full blocks ----
+  if (nc + ns > 0) {
+    u32x16 qf_lo, qf_hi, addr;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const u32x4 lo = __builtin_bit_cast(u32x4, qf[kk]), hi = __builtin_bit_cast(u32x4, qf[kk + 4]);
+      qf_lo[4 * kk] = lo.x; qf_lo[4 * kk + 1] = lo.y; qf_lo[4 * kk + 2] = lo.z; qf_lo[4 * kk + 3] = lo.w;
+      qf_hi[4 * kk] = hi.x; qf_hi[4 * kk + 1] = hi.y; qf_hi[4 * kk + 2] = hi.z; qf_hi[4 * kk + 3] = hi.w;
+    }
+    const uint32_t lds0 = uint32_t(uintptr_t((__attribute__((address_space(3))) unsigned char *)smem));
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) addr[kk] = uint32_t(uintptr_t((__attribute__((address_space(3))) const unsigned char *)kaddr[kk]));
+#pragma unroll
+    for (int db = 0; db < DB; ++db) addr[8 + db] = uint32_t(uintptr_t((__attribute__((address_space(3))) const unsigned char *)vaddr[db]));
+    addr[12] = uint32_t(lr * cpitch + kcol);
+    addr[13] = uint32_t(lr * cpitch + vcol);
+    addr[14] = uint32_t(lr * spitch + kcol);
+    addr[15] = uint32_t(lr * spitch + vcol);
+    const uint64_t kc_base = reinterpret_cast<uint64_t>(kc), vc_base = reinterpret_cast<uint64_t>(vc);
+    const uint64_t ks_base = reinterpret_cast<uint64_t>(ks), vs_base = reinterpret_cast<uint64_t>(vs);
+    const uint32_t cstep = uint32_t(32 * cpitch), sstep = uint32_t(32 * spitch);
+    const uint32_t nc_u = uint32_t(nc), nb = uint32_t(nc + ns);
+    const uint32_t ldsk = lds0 + 1024u * uint32_t(wave_s);
+    float nm = -mref;
+    {
+      const uint32_t nc = nc_u;  // (the name the generated statement uses)
+#include "lsp_attn_pipe_loop.inc"
+    }
+    mref = -nm;
+  }
+
+  lsum = half_sum(lsum);
+  if (qi < N) {
+    const float inv = 1.0f / lsum;
+    uint16_t *op = static_cast<uint16_t *>(a.out) + b * a.os[0] + int64_t(qi) * a.os[1] + h * a.os[2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        u32x2 w;
+        w.x = pack_bf16(oacc[db][4 * r4] * inv, oacc[db][4 * r4 + 1] * inv);
+        w.y = pack_bf16(oacc[db][4 * r4 + 2] * inv, oacc[db][4 * r4 + 3] * inv);
+        *reinterpret_cast<u32x2 *>(op + 32 * db + 8 * r4 + 4 * hf) = w;
+      }
+  }
+}
+
+int32_t launch_pipe(AttnArgs a, const AttnLayers &layers, hipStream_t st) {
+  const int64_t nwg = place_grid(a, 256);
+  if (nwg > 0x7fffffff) {
+    set_error("lsp_attn_step: launch of %lld workgroups is too large", (long long)nwg);
+    return LSP_ERR_UNSUPPORTED;
+  }
+  const size_t lds_ring = size_t(8) * 2 * 32 * 256;
+  const size_t lds_split = 8 * size_t(Geo<128>::WAVE_LDS) + 32 * size_t(Geo<128>::KPITCH);
+  const size_t lds = lds_ring > lds_split ? lds_ring : lds_split;
+  auto kern = attn_bf16_pipe_kernel;
+  static std::atomic<uint64_t> configured{0};
+  if (const int32_t rc = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, configured, "lsp_attn_step: hipFuncSetAttribute")) return rc;
+  kern<<<dim3(static_cast<unsigned>(nwg), layers.n > 0 ? layers.n : 1, 1), 512, lds, st>>>(a, layers);
+  LSP_CHECK_LAUNCH("lsp_attn_step: bf16 pipelined launch");
+  return LSP_OK;
+}
+
 // contiguous cache, or rows through an index (Scattered-Margin measurement)
 template <int D, int WM, int WK>
 int32_t launch(const AttnArgs &a, const AttnLayers &layers, hipStream_t st) {
@@ -1021,7 +1187,10 @@ int32_t dispatch(const AttnArgs &a, const AttnLayers &layers, hipStream_t st) {
   const int64_t rows = int64_t(a.B) * a.Hq * a.S * (layers.n > 0 ? layers.n : 1);
   if (rows / 128 >= 256) {
     if constexpr (D == 128) {
-      if (a.S > 128) return a.cache_rows ? launch_ring_g<8, 4, true>(a, layers, st) : launch_ring_g<8, 4, false>(a, layers, st);
+      // suffix buffers of more than 128 rows: the hand-scheduled loop (its loads keep a row's byte offset inside
+      // a 32-row block in 32 bits, which the row-stride limit of the entry point guarantees); an indexed cache
+      // keeps the compiler-scheduled ring kernel
+      if (a.S > 128) return a.cache_rows ? launch_ring_g<8, 4, true>(a, layers, st) : launch_pipe(a, layers, st);
     }
     return launch_tile<D, 4, 2, 4>(a, layers, st);
   }
