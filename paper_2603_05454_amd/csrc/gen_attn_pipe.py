@@ -60,7 +60,7 @@ NM, LSUM, BM, BSUM, X0, X1, X2, X3 = 168, 169, 170, 171, 172, 173, 174, 175
 O = [176 + 16 * d for d in range(4)]
 
 # scratch SGPRs
-SG = dict(m0save=64, kp=66, vp=68, step=70, li=71, jn=72)
+SG = dict(m0save=64, kp=66, vp=68, step=70, li=71, jn=72, sw=73, t=74)
 
 
 def vr(a, n=1):
@@ -102,29 +102,30 @@ def switch_to_suffix(E):
 
 def load_block(E, stage, tag):
     """Request the next block of the key stream into `stage` (2 wave-wide loads: this
-    wave's 4 K rows and 4 V rows); beyond the last block the last one is requested
-    again (into a stage nobody reads) so that the number of loads in flight is fixed."""
-    li, kp, vp, step = SG["li"], SG["kp"], SG["vp"], SG["step"]
-    E.e(f"s_cmp_lt_u32 s{li}, %[nb]")
-    E.e(f"s_cbranch_scc0 .Lissue_{tag}_%=")
-    E.e(f"s_cmp_eq_u32 s{li}, %[nc]")
-    E.e(f"s_cbranch_scc0 .Lissue_{tag}_%=")
-    switch_to_suffix(E)
+    wave's 4 K rows and 4 V rows); beyond the last block the pointers stay, so the last
+    block is requested again (into a stage nobody reads) and the number of loads in
+    flight is fixed.  The switch from cache rows to suffix rows is out of line."""
+    li, kp, vp, step, t = SG["li"], SG["kp"], SG["vp"], SG["step"], SG["t"]
+    E.e(f"s_cmp_eq_u32 s{li}, s{SG['sw']}")
+    E.e(f"s_cbranch_scc1 .Lswitch_{tag}_%=")
     E.e(f".Lissue_{tag}_%=:")
     E.e(f"s_add_u32 m0, %[ldsk], {stage * TILE}")
-    E.e("s_nop 0")
+    E.e(f"s_add_u32 s{li}, s{li}, 1")
     E.e(f"global_load_lds_dwordx4 v{KOFF}, s[{kp}:{kp + 1}]")
     E.e(f"s_add_u32 m0, %[ldsk], {VBASE + stage * TILE}")
-    E.e("s_nop 0")
-    E.e(f"global_load_lds_dwordx4 v{VOFF}, s[{vp}:{vp + 1}]")
-    E.e(f"s_add_u32 s{li}, s{li}, 1")
     E.e(f"s_cmp_lt_u32 s{li}, %[nb]")
-    E.e(f"s_cbranch_scc0 .Lloaded_{tag}_%=")
-    E.e(f"s_add_u32 s{kp}, s{kp}, s{step}")
+    E.e(f"global_load_lds_dwordx4 v{VOFF}, s[{vp}:{vp + 1}]")
+    E.e(f"s_cselect_b32 s{t}, s{step}, 0")
+    E.e(f"s_add_u32 s{kp}, s{kp}, s{t}")
     E.e(f"s_addc_u32 s{kp + 1}, s{kp + 1}, 0")
-    E.e(f"s_add_u32 s{vp}, s{vp}, s{step}")
+    E.e(f"s_add_u32 s{vp}, s{vp}, s{t}")
     E.e(f"s_addc_u32 s{vp + 1}, s{vp + 1}, 0")
-    E.e(f".Lloaded_{tag}_%=:")
+
+
+def switch_code(E, tag):
+    E.e(f".Lswitch_{tag}_%=:")
+    switch_to_suffix(E)
+    E.e(f"s_branch .Lissue_{tag}_%=")
 
 
 def read_k_frags(E, stage, ks):
@@ -133,31 +134,22 @@ def read_k_frags(E, stage, ks):
 
 
 def block_max(E, sn, part):
-    """Maximum of the 16 scores of register block sn, in four parts; the last part
-    folds the two half-columns (lanes l and l+32 hold the two key halves of a
-    query) and scales to the log2 domain."""
+    """Maximum of this lane's 16 scores of register block sn (raw, unscaled), in three parts.
+    The fold over the two lanes of a query happens on the cold path only."""
     if part == 0:
         E.e(f"v_max_f32 v{BM}, v{sn[0]}, v{sn[1]}")
         E.e(f"v_max3_f32 v{BM}, v{BM}, v{sn[2]}, v{sn[3]}")
-    elif part in (1, 2):
+    else:
         for r in range(4 + 6 * (part - 1), 10 + 6 * (part - 1), 2):
             E.e(f"v_max3_f32 v{BM}, v{BM}, v{sn[r]}, v{sn[r + 1]}")
-    else:
-        E.e(f"v_mov_b32 v{X0}, v{BM}")
-        E.e(f"v_mov_b32 v{X1}, v{BM}")
-        E.e("s_nop 1")
-        E.e(f"v_permlane32_swap_b32 v{X0}, v{X1}")
-        E.e("s_nop 1")
-        E.e(f"v_max_f32 v{BM}, v{X0}, v{X1}")
-        E.e(f"v_mul_f32 v{BM}, %[sc], v{BM}")
 
 
 def iteration(E, u):
     """Block j = 8n + u: soft-max of S(j) under S(j+1) = K(j+1).Q^T, then O += V(j)^T.P(j)^T."""
     cur, nxt = S[u & 1], S[(u + 1) & 1]
     # reference check on the maximum of S(j) (computed while the previous block's second product ran)
-    E.e(f"v_add_f32 v{X0}, v{BM}, v{NM}")
-    E.e(f"v_mov_b32 v{BSUM}, 0")
+    # (any lane's own half-column above the reference by 8 octaves sends the wave to the cold path)
+    E.e(f"v_fma_f32 v{X0}, v{BM}, %[sc], v{NM}")
     E.e(f"v_cmp_lt_f32 vcc, 0x41000000, v{X0}")
     E.e(f"s_cbranch_vccnz .Lresc_{u}_%=")
     E.e(f".Lafter_{u}_%=:")
@@ -173,11 +165,12 @@ def iteration(E, u):
 
     def stage_c(i):
         E.e(f"v_cvt_pk_bf16_f32 v{PF[i]}, v{T[2 * i]}, v{T[2 * i + 1]}")
-        E.e(f"v_dot2c_f32_bf16 v{BSUM}, 0x3f803f80, v{PF[i]}")
+        E.e(f"v_dot2c_f32_bf16 v{LSUM}, 0x3f803f80, v{PF[i]}")
 
     # first product of the NEXT block, soft-max of this one, V^T fragment reads of this one
     for kk in range(8):
-        E.need(KF[kk])
+        if kk % 4 == 0:
+            E.need(*KF[kk:kk + 4])
         c = vr(nxt[0], 16) if kk else "0"
         E.e(f"v_mfma_f32_32x32x16_bf16 {vr(nxt[0], 16)}, {vr(KF[kk], 4)}, {vr(QF[kk], 4)}, {c}")
         k2, db = kk // 4, kk % 4
@@ -192,7 +185,8 @@ def iteration(E, u):
     for m in range(8):
         k2, db = m // 4, m % 4
         f = 4 * k2 + db
-        E.need(VF[f], VF[f] + 2)
+        if m % 4 == 0:
+            E.need(*[VF[f + d] + h for d in range(4) for h in (0, 2)])
         E.e(f"v_mfma_f32_32x32x16_bf16 {vr(O[db], 16)}, {vr(VF[f], 4)}, {vr(PF[4 * k2], 4)}, {vr(O[db], 16)}")
         if m == 0:
             stage_e(7)
@@ -203,7 +197,6 @@ def iteration(E, u):
             read_k_frags(E, (u + 2) % NS, (0, 1))
         elif m == 3:
             read_k_frags(E, (u + 2) % NS, (2, 3))
-            E.e(f"v_add_f32 v{LSUM}, v{LSUM}, v{BSUM}")
         elif m == 4:
             read_k_frags(E, (u + 2) % NS, (4, 5))
             block_max(E, nxt, 0)
@@ -212,8 +205,6 @@ def iteration(E, u):
             block_max(E, nxt, 1)
         elif m == 6:
             block_max(E, nxt, 2)
-        else:
-            block_max(E, nxt, 3)
     E.e(f"s_add_u32 s{SG['jn']}, s{SG['jn']}, 1")
     E.e(f"s_cmp_lt_u32 s{SG['jn']}, %[nb]")
     E.e("s_cbranch_scc0 .Lexit_%=")
@@ -227,7 +218,16 @@ def rescale(E, u):
     take it as the new reference; sums and accumulators are scaled by 2^(old - new)."""
     E.e(f".Lresc_{u}_%=:")
     E.e("s_nop 15")                                        # the accumulators were written by matrix instructions
+    E.e(f"v_mov_b32 v{X1}, v{BM}")                         # fold the two lanes of a query: both get the column maximum
+    E.e("s_nop 1")
+    E.e(f"v_permlane32_swap_b32 v{BM}, v{X1}")
+    E.e("s_nop 1")
+    E.e(f"v_max_f32 v{BM}, v{BM}, v{X1}")
+    E.e(f"v_mul_f32 v{BM}, %[sc], v{BM}")                  # log2 domain
+    E.e(f"v_add_f32 v{X0}, v{BM}, v{NM}")
+    E.e(f"v_cmp_lt_f32 vcc, 0x41000000, v{X0}")            # per query now (the same in both of its lanes)
     E.e(f"v_xor_b32 v{X1}, 0x80000000, v{NM}")             # old reference
+    E.e("s_nop 1")
     E.e(f"v_cndmask_b32 v{X2}, v{X1}, v{BM}, vcc")         # new reference: the block maximum where vcc, else the old one
     E.e(f"v_sub_f32 v{X3}, v{X1}, v{X2}")
     E.e("s_nop 0")
@@ -250,6 +250,9 @@ def generate():
     E.e(f"s_mov_b32 s{step}, %[cstep]")
     E.e(f"s_mov_b32 s{li}, 0")
     E.e(f"s_mov_b32 s{jn}, 0")
+    # index of the block at which the stream switches from cache rows to suffix rows (none: never)
+    E.e("s_cmp_lt_u32 %[nc], %[nb]")
+    E.e(f"s_cselect_b32 s{SG['sw']}, %[nc], -1")
     for t in range(LA):
         load_block(E, t, f"p{t}")
     # blocks 0..3 have landed everywhere
@@ -264,7 +267,7 @@ def generate():
     E.e("s_nop 7")
     read_k_frags(E, 1, range(8))
     E.e("s_nop 7")
-    for part in range(4):
+    for part in range(3):
         block_max(E, S[0], part)
     E.e(".Lloop_%=:")
     for u in range(NS):
@@ -277,6 +280,9 @@ def generate():
     E.e("s_branch .Lend_%=")
     for u in range(NS):
         rescale(E, u)
+        switch_code(E, f"i{u}")
+    for t in range(LA):
+        switch_code(E, f"p{t}")
     E.e(".Lend_%=:")
     return E.lines
 
