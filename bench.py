@@ -74,7 +74,8 @@ def parse():
 # --------------------------------------------------------------------------- #
 def parse_traffic(path=os.path.join(ROOT, TRAFFIC_FILE)):
     """{workload: {kernel name: {counter: units per dispatch}}} and the KiB-per-unit scale of
-    each counter (from the 1 GiB copy in the same file).  Empty when the file is missing."""
+    each counter (from the 1 GiB copy in the same file).  Empty when the file is missing.
+    table[workload]["layers"] = layer count of the profiled run ("-- workload c4 layers=2")."""
     table, scale = {}, {}
     try:
         text = open(path).read()
@@ -82,9 +83,10 @@ def parse_traffic(path=os.path.join(ROOT, TRAFFIC_FILE)):
         return table, scale
     sect = "calibration"
     for line in text.splitlines():
-        m = re.match(r"-- workload (\w+)", line)
+        m = re.match(r"-- workload (\w+)(?: layers=(\d+))?", line)
         if m:
             sect = m.group(1)
+            table.setdefault(sect, {})["layers"] = int(m.group(2) or 1)
             continue
         m = re.match(r"(\S.*?)\s+(FETCH_SIZE|WRITE_SIZE)\s+dispatches=\s*(\d+)\s+avg_per_dispatch=\s*([0-9.]+)", line)
         if not m:
@@ -98,18 +100,23 @@ def parse_traffic(path=os.path.join(ROOT, TRAFFIC_FILE)):
     return table, scale
 
 
-def traffic_for(workload, call):
-    """Measured HBM bytes per launch of `call` at `workload` (read + written), or None when the
-    committed summary has no line for every kernel of that call."""
+def traffic_for(workload, call, layers=1):
+    """Measured HBM bytes per launch of `call` at `workload` with `layers` layers (read + written), or
+    None when the committed summary has no line for every kernel of that call.  The attention and
+    append kernels move bytes in proportion to the layer count of a launch: their counters are taken
+    per layer of the profiled run and multiplied by `layers`."""
     table, scale = parse_traffic()
     sec = table.get(workload)
     if not sec or not scale:
         return None
     total, found = 0.0, 0
     for kern, ctrs in sec.items():
-        if kern.startswith(KERNELS_OF[call]) and "FETCH_SIZE" in ctrs and "WRITE_SIZE" in ctrs:
-            total += (ctrs["FETCH_SIZE"] * scale["FETCH_SIZE"] + ctrs["WRITE_SIZE"] * scale["WRITE_SIZE"]) * 1024
-            found += 1
+        if kern == "layers" or not kern.startswith(KERNELS_OF[call]) or "FETCH_SIZE" not in ctrs or "WRITE_SIZE" not in ctrs:
+            continue
+        per_layer = kern.startswith(("attn_", "append_kernel"))
+        f = layers / sec["layers"] if per_layer else 1.0
+        total += (ctrs["FETCH_SIZE"] * scale["FETCH_SIZE"] + ctrs["WRITE_SIZE"] * scale["WRITE_SIZE"]) * 1024 * f
+        found += 1
     return round(total) if found >= len(KERNELS_OF[call]) else None
 
 
@@ -295,15 +302,13 @@ def run_workload(name, K, Wm, layers=0, use_graph=True, cpu_baseline=True, cpu_b
     share = {k: v["s"] for k, v in kernels.items()}
     dom = max(share, key=share.get)
     kd = kernels[dom]
-    traffic = traffic_for(name, dom)
-    if traffic is not None and dom == "lsp_attn_step":
-        traffic *= w.layers          # the counter summary is per layer; one launch covers all layers
+    traffic = traffic_for(name, dom, w.layers)
     path_bytes = conf_bytes + append_bytes
     roofline = {"kernel": dom, "bound": kd["bound"], "achieved": round(kd["achieved"], 2), "peak": kd["peak"],
                 "unit": kd["unit"], "frac": round(kd["achieved"] / kd["peak"], 4),
                 "traffic": traffic,
                 "traffic_unit": f"HBM bytes per launch, read + written: rocprofv3 FETCH_SIZE / WRITE_SIZE in {TRAFFIC_FILE}"
-                                + (f", one layer's figure x {w.layers} layers" if dom == "lsp_attn_step" and w.layers > 1 else ""),
+                                + (f", per-layer figure of the profiled run x {w.layers} layers" if dom == "lsp_attn_step" and w.layers > 1 else ""),
                 "avg_launch_us": round(kd["s"] * 1e6, 2),
                 "launch": (f"one launch = all {w.layers} layers" if dom == "lsp_attn_step" else "one launch per step"),
                 "all": {k: {"avg_us": round(v["s"] * 1e6, 2), "bound": v["bound"], "achieved": round(v["achieved"], 2),
@@ -685,28 +690,40 @@ def calibrate_copy():
 
 
 def calibrate_read():
-    """What a bare streaming read of configuration 2's logits (64.7 MB, cold: rotated over 12
-    buffers) costs end to end on this chip: a reduction that reads every byte once and writes
-    one value per workgroup (torch's sum over int32 words).  This bounds lsp_confidence at
-    that size from below; the figure is the mean over graph-replayed launches."""
+    """What a bare streaming read of configuration 2's logits (256 rows x 126 464 bf16 = 64.7 MB,
+    cold: rotated over 12 buffers, one workgroup of 512 threads per row like lsp_confidence there)
+    costs end to end on this chip, and the streaming rate of a 2 GiB read.  lsp_bench_read does
+    nothing but load and XOR: this bounds lsp_confidence at that size from below.  Launched the
+    way the timed step is (replayed from a captured graph), HIP events around the replays."""
     import torch
-    n = 256 * 126464 * 2 // 4
-    bufs = [torch.randint(0, 100, (n,), dtype=torch.int32, device="cuda:0") for _ in range(12)]
-    big = torch.randint(0, 100, (512 << 20,), dtype=torch.int32, device="cuda:0")       # 2 GiB: the streaming rate
-    out = torch.empty((), dtype=torch.int64, device="cuda:0")
+    import paper_2603_05454_amd as lsp
+    n = 256 * 126464 * 2
+    bufs = [torch.randint(0, 100, (n // 4,), dtype=torch.int32, device="cuda:0") for _ in range(12)]
+    big = torch.randint(0, 100, (512 << 20,), dtype=torch.int32, device="cuda:0")
+    out = torch.zeros(8192, dtype=torch.int32, device="cuda:0")
     res = {}
-    for name, fn, reps, nbytes in (("read_64.7MB", lambda i: torch.sum(bufs[i % 12], dtype=torch.int64, out=out), 120, n * 4),
-                                   ("read_2GiB", lambda i: torch.sum(big, dtype=torch.int64, out=out), 10, big.numel() * 4)):
+    for name, fn, reps, nbytes in (("read_64.7MB_256_workgroups", lambda i: lsp.bench_read(bufs[i % 12], 256, out), 120, n),
+                                   ("read_64.7MB_2048_workgroups", lambda i: lsp.bench_read(bufs[i % 12], 2048, out), 120, n),
+                                   ("read_2GiB_8192_workgroups", lambda i: lsp.bench_read(big, 8192, out), 10, big.numel() * 4)):
         for i in range(12):
             fn(i)
         torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for i in range(reps):
-            fn(i)
-        b.record()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(reps):
+                fn(i)
+        g.replay()
         torch.cuda.synchronize()
-        t = a.elapsed_time(b) * 1e-3 / reps
+        total, k = 0.0, 0
+        while total < MIN_TIMED_MS and k < 50:
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            g.replay()
+            b.record()
+            torch.cuda.synchronize()
+            total += a.elapsed_time(b)
+            k += 1
+        t = total * 1e-3 / (k * reps)
         res[name] = {"bytes": nbytes, "us": round(t * 1e6, 2), "GBs": round(nbytes / t / 1e9, 1)}
     print(json.dumps({"calibrate_read": res}))
 

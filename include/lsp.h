@@ -349,6 +349,17 @@ int32_t lsp_flip_update(const int32_t *top1_id, int32_t B, int32_t S, int32_t G,
                         int64_t *counters, int32_t window_lo, int32_t window_hi,
                         int32_t *step_counts, void *stream);
 
+/* ------------------------------------------------------------------------- *
+ * Measurement helper (used by the benchmark, not part of the scheduler step):
+ * a bare streaming read of `bytes` bytes of device memory by `workgroups`
+ * workgroups of 512 threads (16-byte non-temporal loads, each workgroup one
+ * contiguous segment; bytes must be a multiple of 16 * workgroups), XOR-folded
+ * into out[workgroups] (device uint32, accumulated).  What it takes is the
+ * floor under lsp_confidence for logits of that size: the one pass over the
+ * logits that Eq. 1 needs, with nothing computed.
+ * ------------------------------------------------------------------------- */
+int32_t lsp_bench_read(const void *buffer, int64_t bytes, int32_t workgroups, uint32_t *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

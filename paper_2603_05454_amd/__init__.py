@@ -47,7 +47,7 @@ EXPORTS = ["lsp_version", "lsp_last_error", "lsp_attn_workspace_bytes", "lsp_att
            "lsp_confidence_workspace_bytes", "lsp_confidence", "lsp_confidence_static_scratch_bytes",
            "lsp_confidence_static", "lsp_commit_workspace_bytes",
            "lsp_commit", "lsp_flip_update", "lsp_select_scattered", "lsp_kv_gather_append",
-           "lsp_attn_step_gather", "lsp_lm_head_confidence_workspace_bytes", "lsp_lm_head_confidence"]
+           "lsp_attn_step_gather", "lsp_lm_head_confidence_workspace_bytes", "lsp_lm_head_confidence", "lsp_bench_read"]
 
 
 def lib() -> ctypes.CDLL:
@@ -64,7 +64,7 @@ def lib() -> ctypes.CDLL:
                   "lsp_lm_head_confidence_workspace_bytes", "lsp_confidence_static_scratch_bytes"):
             getattr(L, n).restype = ctypes.c_size_t
         for n in ("lsp_attn_step", "lsp_attn_step_layers", "lsp_confidence", "lsp_confidence_static", "lsp_commit", "lsp_flip_update", "lsp_select_scattered",
-                  "lsp_kv_gather_append", "lsp_attn_step_gather", "lsp_lm_head_confidence"):
+                  "lsp_kv_gather_append", "lsp_attn_step_gather", "lsp_lm_head_confidence", "lsp_bench_read"):
             getattr(L, n).restype = ctypes.c_int32
         _lib = L
     return _lib
@@ -357,3 +357,11 @@ def kv_gather_append(sel_index, count, prefix_len, layers: LayerTable, appended=
                                     _ptr(appended), _stream())
     _check(rc, "lsp_kv_gather_append")
     return appended
+
+
+def bench_read(buffer, workgroups, out):
+    """lsp_bench_read: bare streaming read of a device buffer (measurement helper)."""
+    _dev(buffer, out)
+    nbytes = buffer.numel() * buffer.element_size()
+    rc = lib().lsp_bench_read(_ptr(buffer), ctypes.c_int64(nbytes), int(workgroups), _ptr(out), _stream())
+    _check(rc, "lsp_bench_read")

@@ -198,7 +198,10 @@ struct LayerPtrs {
   char *dst[2 * kMaxLayersPerLaunch];
 };
 
-// grid: (chunks of NT*VECS*16 bytes covering S rows, B, 2 * layers in this launch).
+// grid: (workgroups per block copy, B, 2 * layers in this launch); a workgroup walks the
+// block in chunks of NT*VECS*16 bytes with stride gridDim.x chunks.  (The commit length is
+// only known on the device; a grid sized for S rows per copy costs a quarter of a
+// millisecond in launch-and-exit alone when a decode step commits a few rows.)
 // prefix_len already holds P + L; the block starts at row P = prefix_len - L.
 template <int NT, int VECS>
 __global__ __launch_bounds__(NT) void append_kernel(
@@ -208,21 +211,22 @@ __global__ __launch_bounds__(NT) void append_kernel(
   const int b = blockIdx.y;
   const int L = commit_len[b];
   const int64_t total = int64_t(L) * row_bytes;
-  const int64_t off0 = int64_t(blockIdx.x) * kBytes;
-  if (off0 >= total) return;
+  if (int64_t(blockIdx.x) * kBytes >= total) return;
   const int P = prefix_len[b] - L;
   const char *src = ptrs.src[blockIdx.z] + int64_t(b) * suf_batch_bytes;
   char *dst = ptrs.dst[blockIdx.z] + int64_t(b) * cache_batch_bytes + int64_t(P) * row_bytes;
-  u32x4 v[VECS];
+  for (int64_t off0 = int64_t(blockIdx.x) * kBytes; off0 < total; off0 += int64_t(gridDim.x) * kBytes) {
+    u32x4 v[VECS];
 #pragma unroll
-  for (int k = 0; k < VECS; ++k) {
-    const int64_t o = off0 + (int64_t(k) * NT + threadIdx.x) * 16;
-    if (o < total) v[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
-  }
+    for (int k = 0; k < VECS; ++k) {
+      const int64_t o = off0 + (int64_t(k) * NT + threadIdx.x) * 16;
+      if (o < total) v[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
+    }
 #pragma unroll
-  for (int k = 0; k < VECS; ++k) {
-    const int64_t o = off0 + (int64_t(k) * NT + threadIdx.x) * 16;
-    if (o < total) __builtin_nontemporal_store(v[k], reinterpret_cast<u32x4 *>(dst + o));
+    for (int k = 0; k < VECS; ++k) {
+      const int64_t o = off0 + (int64_t(k) * NT + threadIdx.x) * 16;
+      if (o < total) __builtin_nontemporal_store(v[k], reinterpret_cast<u32x4 *>(dst + o));
+    }
   }
 }
 
@@ -230,7 +234,14 @@ template <int NT, int VECS>
 void launch_append(const LayerPtrs &p, int64_t max_bytes, int B, int nl, hipStream_t st, int64_t row_bytes,
                    int64_t suf_bb, int64_t cache_bb, const int32_t *prefix_len, const int32_t *commit_len) {
   constexpr int kBytes = NT * VECS * 16;
-  const unsigned chunks = unsigned((max_bytes + kBytes - 1) / kBytes);
+  // enough workgroups to fill the chip when whole suffixes are committed (about 64 K in all), never more
+  // than the block has chunks
+  const int64_t all_chunks = (max_bytes + kBytes - 1) / kBytes;
+  const int64_t copies = int64_t(B) * 2 * nl;
+  int64_t per_copy = (65536 + copies - 1) / copies;
+  if (per_copy > all_chunks) per_copy = all_chunks;
+  if (per_copy < 1) per_copy = 1;
+  const unsigned chunks = unsigned(per_copy);
   append_kernel<NT, VECS><<<dim3(chunks, B, 2 * nl), NT, 0, st>>>(p, row_bytes, suf_bb, cache_bb, prefix_len, commit_len);
 }
 

@@ -68,8 +68,41 @@ __global__ __launch_bounds__(256) void flip_kernel(
   }
 }
 
+// Measurement helper: a bare streaming read.  Workgroup w reads segment w of the buffer
+// with 16-byte non-temporal loads, four in flight per lane, and folds them with XOR; one
+// word per workgroup is written.  This is the floor under any kernel that has to read a
+// buffer of that size once (launch, first loads, drain included).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(512) void read_kernel(const u32x4 *__restrict__ p, int64_t vec_per_wg,
+                                                   uint32_t *__restrict__ out) {
+  const u32x4 *q = p + int64_t(blockIdx.x) * vec_per_wg;
+  u32x4 acc = {0, 0, 0, 0};
+  int64_t i = threadIdx.x;
+  for (; i + 3 * 512 < vec_per_wg; i += 4 * 512) {
+    const u32x4 a = __builtin_nontemporal_load(q + i), b = __builtin_nontemporal_load(q + i + 512);
+    const u32x4 c = __builtin_nontemporal_load(q + i + 1024), d = __builtin_nontemporal_load(q + i + 1536);
+    acc ^= a ^ b ^ c ^ d;
+  }
+  for (; i < vec_per_wg; i += 512) acc ^= __builtin_nontemporal_load(q + i);
+  uint32_t v = acc.x ^ acc.y ^ acc.z ^ acc.w;
+#pragma unroll
+  for (int m = 1; m < kWave; m <<= 1) v ^= __shfl_xor(v, m);
+  if ((threadIdx.x & (kWave - 1)) == 0) atomicXor(&out[blockIdx.x], v);
+}
+
 }  // namespace
 }  // namespace lsp
+
+extern "C" int32_t lsp_bench_read(const void *buffer, int64_t bytes, int32_t workgroups, uint32_t *out, void *stream) {
+  using namespace lsp;
+  LSP_CHECK_ARG(buffer && out && bytes > 0 && workgroups > 0, "lsp_bench_read: bad argument");
+  LSP_CHECK_ARG(aligned16(buffer) && bytes % (int64_t(workgroups) * 16) == 0,
+                "lsp_bench_read: buffer must be 16-byte aligned and split evenly into 16-byte vectors per workgroup");
+  read_kernel<<<workgroups, 512, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const u32x4 *>(buffer),
+                                                                         bytes / (int64_t(workgroups) * 16), out);
+  LSP_CHECK_LAUNCH("lsp_bench_read: launch");
+  return LSP_OK;
+}
 
 extern "C" const char *lsp_version(void) { return "liblsp 0.1 (gfx950)"; }
 extern "C" const char *lsp_last_error(void) { return lsp::g_error; }
