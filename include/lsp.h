@@ -360,6 +360,21 @@ int32_t lsp_flip_update(const int32_t *top1_id, int32_t B, int32_t S, int32_t G,
  * ------------------------------------------------------------------------- */
 int32_t lsp_bench_read(const void *buffer, int64_t bytes, int32_t workgroups, uint32_t *out, void *stream);
 
+/* ------------------------------------------------------------------------- *
+ * Measurement helper (used by the benchmark, not part of the scheduler step):
+ * a bare loop of v_mfma_f32_32x32x16_bf16 with no memory traffic inside it,
+ * `workgroups` workgroups of 512 threads (two waves per SIMD), `iters`
+ * iterations of 8 matrix instructions per wave = workgroups * 8 * iters * 8 *
+ * 32768 flop per launch.  operands: device buffer of 16 * 512 * 16 bytes (per
+ * lane 8 A and 8 B fragments of 8 bf16, fragment s of lane t at 16-byte vector
+ * s * 512 + t, B fragments after the A fragments), read once per lane.
+ * out: device float [workgroups * 512], overwritten (keeps the loop alive).
+ * The rate it sustains depends on the operand VALUES (the chip lowers its
+ * clock under the power that random operands draw), which makes it the
+ * matrix-pipe ceiling for the attention of Algorithm 1 line 4 on such data.
+ * ------------------------------------------------------------------------- */
+int32_t lsp_bench_mfma(const void *operands, int32_t iters, int32_t workgroups, float *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

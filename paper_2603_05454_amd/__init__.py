@@ -47,7 +47,7 @@ EXPORTS = ["lsp_version", "lsp_last_error", "lsp_attn_workspace_bytes", "lsp_att
            "lsp_confidence_workspace_bytes", "lsp_confidence", "lsp_confidence_static_scratch_bytes",
            "lsp_confidence_static", "lsp_commit_workspace_bytes",
            "lsp_commit", "lsp_flip_update", "lsp_select_scattered", "lsp_kv_gather_append",
-           "lsp_attn_step_gather", "lsp_lm_head_confidence_workspace_bytes", "lsp_lm_head_confidence", "lsp_bench_read"]
+           "lsp_attn_step_gather", "lsp_lm_head_confidence_workspace_bytes", "lsp_lm_head_confidence", "lsp_bench_read", "lsp_bench_mfma"]
 
 
 def lib() -> ctypes.CDLL:
@@ -64,7 +64,7 @@ def lib() -> ctypes.CDLL:
                   "lsp_lm_head_confidence_workspace_bytes", "lsp_confidence_static_scratch_bytes"):
             getattr(L, n).restype = ctypes.c_size_t
         for n in ("lsp_attn_step", "lsp_attn_step_layers", "lsp_confidence", "lsp_confidence_static", "lsp_commit", "lsp_flip_update", "lsp_select_scattered",
-                  "lsp_kv_gather_append", "lsp_attn_step_gather", "lsp_lm_head_confidence", "lsp_bench_read"):
+                  "lsp_kv_gather_append", "lsp_attn_step_gather", "lsp_lm_head_confidence", "lsp_bench_read", "lsp_bench_mfma"):
             getattr(L, n).restype = ctypes.c_int32
         _lib = L
     return _lib
@@ -365,3 +365,18 @@ def bench_read(buffer, workgroups, out):
     nbytes = buffer.numel() * buffer.element_size()
     rc = lib().lsp_bench_read(_ptr(buffer), ctypes.c_int64(nbytes), int(workgroups), _ptr(out), _stream())
     _check(rc, "lsp_bench_read")
+
+
+MFMA_BENCH_OPERAND_BYTES = 16 * 512 * 16
+MFMA_BENCH_FLOP_PER_WG_ITER = 8 * 8 * 2 * 32 * 32 * 16
+
+
+def bench_mfma(operands, iters, workgroups, out):
+    """lsp_bench_mfma: bare matrix-instruction loop on the given operand values (measurement helper)."""
+    _dev(operands, out)
+    if operands.numel() * operands.element_size() < MFMA_BENCH_OPERAND_BYTES:
+        raise ValueError("bench_mfma: operands must hold 16 * 512 * 16 bytes")
+    if out.numel() < int(workgroups) * 512 or out.dtype != torch.float32:
+        raise ValueError("bench_mfma: out must be float32 [workgroups * 512]")
+    rc = lib().lsp_bench_mfma(_ptr(operands), int(iters), int(workgroups), _ptr(out), _stream())
+    _check(rc, "lsp_bench_mfma")

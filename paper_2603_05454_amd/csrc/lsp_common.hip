@@ -90,8 +90,49 @@ __global__ __launch_bounds__(512) void read_kernel(const u32x4 *__restrict__ p, 
   if ((threadIdx.x & (kWave - 1)) == 0) atomicXor(&out[blockIdx.x], v);
 }
 
+// Measurement helper: a bare matrix-instruction loop (no memory traffic inside the loop).
+// Every lane loads 8 A and 8 B fragments (16 bytes each) once, then issues
+// v_mfma_f32_32x32x16_bf16 over them round robin into four accumulators.  What it sustains
+// depends on the operand VALUES: with random operands the chip lowers its clock to stay inside
+// its power limit, so this is the matrix ceiling a kernel working on such data can be held to.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(512) void mfma_kernel(const u32x4 *__restrict__ operands, int32_t iters,
+                                                   float *__restrict__ out) {
+  u32x4 A[8], B[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    A[s] = operands[s * 512 + threadIdx.x];
+    B[s] = operands[(8 + s) * 512 + threadIdx.x];
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[s & 3]) : "v"(A[s]), "v"(B[(s * 3 + 1) & 7]));
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t += acc[n][r];
+  out[blockIdx.x * 512 + threadIdx.x] = t;
+}
+
 }  // namespace
 }  // namespace lsp
+
+extern "C" int32_t lsp_bench_mfma(const void *operands, int32_t iters, int32_t workgroups, float *out, void *stream) {
+  using namespace lsp;
+  LSP_CHECK_ARG(operands && out && iters > 0 && workgroups > 0, "lsp_bench_mfma: bad argument");
+  LSP_CHECK_ARG(aligned16(operands), "lsp_bench_mfma: operands must be 16-byte aligned");
+  mfma_kernel<<<workgroups, 512, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const u32x4 *>(operands), iters, out);
+  LSP_CHECK_LAUNCH("lsp_bench_mfma: launch");
+  return LSP_OK;
+}
 
 extern "C" int32_t lsp_bench_read(const void *buffer, int64_t bytes, int32_t workgroups, uint32_t *out, void *stream) {
   using namespace lsp;
