@@ -222,11 +222,13 @@ def test_mixed_short_and_long_suffixes_in_one_call(lsp, oracle):
 
 @pytest.mark.parametrize("indexed", [False, True])
 def test_long_suffix_key_block_counts(lsp, oracle, indexed):
-    """Head_dim-128 long-suffix kernel (eight-stage ring, one barrier every four
-    key blocks): per-sequence key counts from 3 to 15 blocks, i.e. fewer blocks
-    than the prefetch depth, every remainder modulo the barrier period, ragged
-    last blocks, and a cache/suffix boundary inside a block; with the cache
-    addressed directly and through a shuffled row index."""
+    """Head_dim-128 long-suffix kernels (eight-stage ring; the hand-scheduled loop
+    with a barrier every second key block for a contiguous cache, the compiler-
+    scheduled one with a barrier every fourth for an indexed cache): per-sequence
+    key counts from 3 to 15 blocks, i.e. fewer blocks than the prefetch depth,
+    every remainder modulo the barrier period, ragged last blocks, and a
+    cache/suffix boundary inside a block; with the cache addressed directly and
+    through a shuffled row index."""
     w = W.scaled(W.C2, B=8, S=160, P=320, C=320, Hq=32, Hkv=8, D=128, seed=123)
     pl = torch.tensor([0, 1, 31, 33, 96, 100, 224, 320], dtype=torch.int32)
     sl = torch.tensor([160, 95, 129, 130, 97, 160, 65, 160], dtype=torch.int32)   # all above the key-split switch
@@ -252,6 +254,29 @@ def test_long_suffix_key_block_counts(lsp, oracle, indexed):
     sel = got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()]
     assert (sel - ref).abs().max().item() <= TOL["bf16"]
     for b in range(w.B):
+        assert torch.all(got[b, int(sl[b]):] == 123.0)
+        assert not torch.isnan(got[b, : int(sl[b])]).any()
+
+
+@pytest.mark.parametrize("S,tail", [(160, 0), (160, 17), (192, 31)])
+def test_long_suffix_every_cache_to_suffix_switch_position(lsp, oracle, S, tail):
+    """The hand-scheduled loop steps from the cache stream to the suffix stream at a
+    block index that differs per sequence: 0 to 19 full cache blocks (more than two
+    turns of the eight-stage ring, both parities of the barrier period) followed by
+    the suffix blocks, with and without ragged cache and suffix tails."""
+    B = 20
+    w = W.scaled(W.C2, B=B, S=S, P=640, C=640, Hq=16, Hkv=4, D=128, seed=500 + S + tail)
+    pl = torch.tensor([32 * k + (tail if k % 3 else 0) for k in range(B)], dtype=torch.int32)
+    sl = torch.tensor([S - (tail if k % 2 else 0) for k in range(B)], dtype=torch.int32)
+    kv = W.make_layer_kv(w, 0, prefix_len=pl)
+    got = _run(lsp, kv, pl, sl)
+    rows = torch.tensor([[b, i, h] for b in range(B) for i in (0, 1, 31, 32, 77, int(sl[b]) - 1) for h in (0, 9, 15)],
+                        dtype=torch.int32)
+    ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl, rows=rows)
+    sel = got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()]
+    err = (sel - ref).abs().reshape(B, -1).max(dim=1).values
+    assert err.max().item() <= TOL["bf16"], err
+    for b in range(B):
         assert torch.all(got[b, int(sl[b]):] == 123.0)
         assert not torch.isnan(got[b, : int(sl[b])]).any()
 
