@@ -165,6 +165,44 @@ def test_full_config_shapes(lsp, oracle, cfg):
     assert torch.all(ref["snapped_boundary"] <= ref["raw_boundary"])
 
 
+@pytest.mark.parametrize("cfg", ["c2", "c3"])
+def test_confidence_then_commit_each_side_on_its_own(lsp, oracle, cfg):
+    """Configs 2 and 3 at full size with NOTHING passed between the two sides: the oracle's
+    commit consumes the oracle's ids and margins (all rows), the library's commit consumes
+    the library's; every output of the pair of calls is then compared (Algorithm 1 lines
+    5 and 7-10 chained)."""
+    w = W.C2 if cfg == "c2" else W.C3
+    z, info = W.make_logits(w)
+    _, bm = W.make_delimiters(w)
+    pl, sl = W.make_lengths(w)
+    layers = [W.make_layer_kv(w, 0)]
+    tokens = W.make_tokens(w, w.C)
+    # oracle side
+    ids_r, p_r, m_r = oracle.confidence(z, sl)
+    lay_r = [{k: v.clone() for k, v in L.items()} for L in layers]
+    pl_r, sl_r, tok_r = pl.clone(), sl.clone(), tokens.clone()
+    ref = oracle.commit(m_r, ids_r, bm, w.V, w.tau, w.window, 1, 1, pl_r, sl_r, tokens=tok_r,
+                        k_suf=[L["k_suf"] for L in lay_r], v_suf=[L["v_suf"] for L in lay_r],
+                        k_cache=[L["k_cache"] for L in lay_r], v_cache=[L["v_cache"] for L in lay_r])
+    # library side
+    lay_g = [{k: v.cuda() for k, v in L.items()} for L in layers]
+    table = lsp.LayerTable([L["k_suf"] for L in lay_g], [L["v_suf"] for L in lay_g],
+                           [L["k_cache"] for L in lay_g], [L["v_cache"] for L in lay_g])
+    pl_g, sl_g, tok_g = pl.cuda(), sl.cuda(), tokens.cuda()
+    ids_g, p_g, m_g = lsp.confidence(z.cuda(), sl_g)
+    got = lsp.commit(m_g, ids_g, bm.cuda(), w.V, w.tau, w.window, 1, 1, pl_g, sl_g, tokens=tok_g, layers=table)
+    torch.cuda.synchronize()
+    act = torch.arange(w.S)[None, :] < sl[:, None]
+    assert torch.equal(ids_g.cpu()[act], ids_r[act]) and torch.equal(m_g.cpu()[act], m_r[act])
+    assert (p_g.cpu()[act] - p_r[act]).abs().max().item() <= 2e-2
+    for k in ref:
+        assert _same(got[k].cpu(), ref[k]), k
+    assert torch.equal(pl_g.cpu(), pl_r) and torch.equal(sl_g.cpu(), sl_r) and torch.equal(tok_g.cpu(), tok_r)
+    for name in ("k_cache", "v_cache"):
+        assert torch.equal(lay_g[0][name].cpu().view(torch.int16), lay_r[0][name].view(torch.int16)), name
+    assert int(ref["commit_len"].sum()) > 0
+
+
 def test_c4_shape_two_layers(lsp, oracle):
     """Config-4 cache geometry (B=8, C=8192, rows of 8 KB), two layers, worst-case
     commit length (tau = -inf, no snap => L = S = 1024 rows per sequence)."""
