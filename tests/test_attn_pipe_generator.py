@@ -1,0 +1,170 @@
+"""Host-side checks of the generated block loop of the long-suffix attention kernel
+(csrc/gen_attn_pipe.py -> csrc/lsp_attn_pipe_loop.inc).  The loop is hand-scheduled text, so
+what a compiler would guarantee is checked here instead, on the CPU, by an independent walk
+over the instruction stream:
+
+  * the committed .inc is exactly what the generator emits;
+  * every register an instruction touches has been waited for if an LDS read that writes it is
+    still in flight (LDS reads complete in order; `s_waitcnt lgkmcnt(n)` leaves at most n
+    outstanding), on the hot path walked twice around the unrolled ring and on every cold
+    block entered from it;
+  * no LDS read lands in a register that the asm statement pins for something else;
+  * wait-count and offset fields fit their encodings, every branch target exists, and no
+    instruction writes memory through the scalar cache or uses packed fp32 arithmetic.
+"""
+import importlib.util
+import os
+import re
+
+import pytest
+
+CSRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2603_05454_amd", "csrc")
+VREG = re.compile(r"\bv\[(\d+):(\d+)\]|\bv(\d+)\b")
+
+
+@pytest.fixture(scope="module")
+def gen():
+    spec = importlib.util.spec_from_file_location("gen_attn_pipe", os.path.join(CSRC, "gen_attn_pipe.py"))
+    m = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(m)
+    return m
+
+
+@pytest.fixture(scope="module")
+def lines(gen):
+    return gen.generate()
+
+
+def _vregs(text):
+    out = set()
+    for m in VREG.finditer(text):
+        if m.group(3) is not None:
+            out.add(int(m.group(3)))
+        else:
+            out.update(range(int(m.group(1)), int(m.group(2)) + 1))
+    return out
+
+
+def _split(line):
+    mnem, _, rest = line.partition(" ")
+    return mnem, rest
+
+
+def test_committed_include_is_what_the_generator_emits(lines):
+    with open(os.path.join(CSRC, "lsp_attn_pipe_loop.inc")) as f:
+        text = f.read()
+    have = re.findall(r'^    "(.*)\\n"$', text, flags=re.M)
+    assert have == lines
+
+
+def test_fields_fit_and_nothing_forbidden(lines):
+    labels = {l[:-1] for l in lines if l.endswith(":")}
+    for l in lines:
+        mnem, rest = _split(l)
+        assert not mnem.startswith(("s_store", "s_buffer_store", "s_atomic", "s_buffer_atomic", "s_dcache", "s_scratch_store")), l
+        assert not mnem.startswith(("v_pk_add_f32", "v_pk_mul_f32", "v_pk_fma_f32")), l
+        for n in re.findall(r"lgkmcnt\((\d+)\)", l):
+            assert 0 <= int(n) <= 15, l
+        for n in re.findall(r"vmcnt\((\d+)\)", l):
+            assert 0 <= int(n) <= 63, l
+        for n in re.findall(r"offset:(\d+)", l):
+            assert 0 <= int(n) <= 65535, l
+        if mnem.startswith(("s_cbranch", "s_branch")):
+            assert rest.strip() in labels, l
+        assert all(r < 256 for r in _vregs(l)), l
+
+
+def test_lds_reads_only_land_in_scratch_registers(gen, lines):
+    pinned = set(range(32, 64)) | set(range(152, 170)) | set(range(176, 240))      # Q fragments, addresses, m and l, O
+    frag = set()
+    for base in gen.KF + gen.VF:
+        frag.update(range(base, base + 4))
+    for l in lines:
+        mnem, rest = _split(l)
+        if mnem.startswith("ds_read"):
+            dst = _vregs(rest.split(",")[0])
+            assert dst and not (dst & pinned), l
+            assert dst <= frag, l
+
+
+def _walk(lines, start, pending, labels, follow_back_edge, max_steps):
+    """Walk from `start` along the hot path (conditional branches not taken, s_branch followed
+    when follow_back_edge says so); returns the list of (index, pending-at-that-point) for every
+    conditional branch passed, and stops at an s_branch it does not follow or after max_steps."""
+    pend = [set(p) for p in pending]
+    seen_cond = []
+    i, steps = start, 0
+    while i < len(lines) and steps < max_steps:
+        l = lines[i]
+        steps += 1
+        if l.endswith(":"):
+            i += 1
+            continue
+        mnem, rest = _split(l)
+        if mnem == "s_waitcnt":
+            m = re.search(r"lgkmcnt\((\d+)\)", l)
+            if m:
+                n = int(m.group(1))
+                pend = pend[len(pend) - n:] if n else []
+            i += 1
+            continue
+        if mnem.startswith("s_cbranch"):
+            seen_cond.append((i, rest.strip(), [set(p) for p in pend]))
+            i += 1
+            continue
+        if mnem == "s_branch":
+            if follow_back_edge(rest.strip()):
+                i = labels[rest.strip()]
+                continue
+            return seen_cond, pend, i
+        touched = _vregs(rest)
+        inflight = set().union(*pend) if pend else set()
+        assert not (touched & inflight), f"line {i}: '{l}' touches {sorted(touched & inflight)} while an LDS read into them is in flight"
+        if mnem.startswith("ds_read"):
+            pend.append(_vregs(rest.split(",")[0]))
+            assert len(pend) <= 16, f"line {i}: more than 16 LDS reads outstanding"
+        i += 1
+    return seen_cond, pend, i
+
+
+def test_every_lds_result_is_waited_for_before_use(lines):
+    labels = {l[:-1]: k for k, l in enumerate(lines) if l.endswith(":")}
+    loop = next(k for k in labels if k.startswith(".Lloop"))
+    # prologue, then twice around the eight unrolled iterations
+    conds, _, _ = _walk(lines, 0, [], labels, lambda t: t == loop, max_steps=len(lines) * 3)
+    assert sum(1 for _, t, _ in conds if t.startswith(".Lexit")) >= 16
+    # every cold block, entered with the in-flight reads of the branch that leads to it
+    checked = 0
+    for idx, target, pend in conds:
+        if target.startswith(".Lexit"):
+            continue
+        sub, _, end = _walk(lines, labels[target], pend, labels, lambda t: False, max_steps=400)
+        assert not sub, (target, "conditional branch inside a cold block")
+        assert lines[end].startswith("s_branch"), target
+        assert not any(lines[k].startswith("ds_read") for k in range(labels[target], end)), target
+        checked += 1
+    assert checked >= 16 + 6
+
+
+def test_exit_drains_every_counter(lines):
+    labels = {l[:-1]: k for k, l in enumerate(lines) if l.endswith(":")}
+    ex = next(v for k, v in labels.items() if k.startswith(".Lexit"))
+    assert lines[ex + 1] == "s_waitcnt vmcnt(0) lgkmcnt(0)"
+
+
+def test_the_checker_sees_a_missing_wait(lines):
+    """The walk above must fail when a wait is taken away: drop, one at a time, a sample of the
+    lgkmcnt waits inside the loop and require an assertion for each."""
+    labels = {l[:-1]: k for k, l in enumerate(lines) if l.endswith(":")}
+    loop_label = next(k for k in labels if k.startswith(".Lloop"))
+    waits = [k for k, l in enumerate(lines) if l.startswith("s_waitcnt lgkmcnt") and k > labels[loop_label]
+             and k < next(v for kk, v in labels.items() if kk.startswith(".Lexit"))]
+    assert len(waits) >= 16
+    caught = 0
+    for k in waits[::3]:
+        broken = lines[:k] + ["s_nop 0"] + lines[k + 1:]
+        try:
+            _walk(broken, 0, [], labels, lambda t: t == loop_label, max_steps=len(lines) * 3)
+        except AssertionError:
+            caught += 1
+    assert caught == len(waits[::3])
