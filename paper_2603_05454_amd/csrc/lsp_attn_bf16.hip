@@ -22,7 +22,7 @@
 // probabilities are then at most 2^8, which bf16 and the fp32 sums hold
 // without loss, and the final division by the row sum removes the offset.
 //
-// Three kernels share that arithmetic:
+// Four kernels share that arithmetic:
 //  * attn_bf16_kernel (short suffixes): a workgroup is WM x WK waves, WM blocks
 //    of 32 queries and a WK-way split of the key range between waves of the
 //    same query block (merged through LDS at the end).  Every wave streams its
@@ -35,9 +35,16 @@
 //    the block), one barrier per block; L1/L2 traffic per flop drops WM-fold,
 //    which is what the matrix cores need once the problem is compute bound.
 //  * attn_bf16_ring_kernel (long suffixes at head_dim 128 with suffix buffers of
-//    more than 128 rows): eight waves, K/V straight from global memory into an
-//    eight-stage LDS ring, one barrier every four blocks; described where it is
-//    defined.
+//    more than 128 rows, cache rows addressed through an index list): eight
+//    waves, K/V straight from global memory into an eight-stage LDS ring, one
+//    barrier every four blocks; described where it is defined.
+//  * attn_bf16_pipe_kernel (the same shapes with a contiguous cache, i.e. the
+//    long-context and decode-loop configurations): the same ring, but the block
+//    loop is a generated, hand-scheduled inline-asm statement
+//    (gen_attn_pipe.py -> lsp_attn_pipe_loop.inc) in which the first product of
+//    block j+1, the soft-max of block j and the second product of block j are
+//    interleaved instruction by instruction; ragged first/last blocks and
+//    short sequences are handled in C++ around it.
 #include "lsp_attn.h"
 
 namespace lsp {
