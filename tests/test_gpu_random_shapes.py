@@ -204,7 +204,54 @@ def _scattered_trial(lsp, oracle, rng):
             assert torch.equal(Lg[name].cpu().view(view), Lr[name].view(view)), (case, name)
 
 
-TRIALS = {"attention": (_attention_trial, 150), "confidence": (_confidence_trial, 150),
+def _long_suffix_trial(lsp, oracle, rng):
+    """Shapes that take the long-suffix head_dim-128 kernels (the hand-scheduled loop for a contiguous
+    cache, the compiler-scheduled ring for an indexed one): enough (sequence, head, row) triples, suffix
+    buffers of more than 128 rows, per-sequence lengths that are full, ragged, a multiple of 32, below
+    the key-split switch, or zero."""
+    Hkv = rng.choice([1, 2, 4, 8])
+    Hq = Hkv * rng.choice([1, 2, 4, 7])
+    S = rng.choice([129, 160, 200, 256, 257, 300, 384, 511, 640])
+    B = max(1, -(-32768 // (Hq * S))) + rng.randint(0, 2)
+    C = rng.choice([64, 200, 512, 700, 1300])
+    w = W.scaled(W.C2, dtype="bf16", B=B, S=S, P=C, C=C, Hq=Hq, Hkv=Hkv, D=128, seed=rng.randint(0, 10**6))
+    pl = torch.tensor([rng.choice([0, C, rng.randint(0, C), 32 * rng.randint(0, C // 32), 31, 33]) for _ in range(B)],
+                      dtype=torch.int32).clamp(max=C)
+    sl = torch.tensor([rng.choice([S, S, rng.randint(0, S), 32 * rng.randint(0, S // 32), rng.randint(0, 70), 0, 1, 64, 65])
+                       for _ in range(B)], dtype=torch.int32).clamp(max=S)
+    kv = W.make_layer_kv(w, 0, prefix_len=pl)
+    g = {k: v.cuda() for k, v in kv.items()}
+    index = None
+    if rng.random() < 0.25:
+        gen = torch.Generator().manual_seed(rng.randint(0, 10**6))
+        index = torch.stack([torch.randperm(C, generator=gen) for _ in range(B)]).to(torch.int32)
+        for name in ("k_cache", "v_cache"):
+            sh = torch.full_like(kv[name], float("nan"))
+            for b in range(B):
+                sh[b][index[b, : int(pl[b])].long()] = kv[name][b, : int(pl[b])]
+            g[name] = sh.cuda()
+    out = torch.full(g["q"].shape, 123.0, dtype=g["q"].dtype, device="cuda")
+    lsp.attn_step(g["q"], g["k_suf"], g["v_suf"], g["k_cache"], g["v_cache"], pl.cuda(), sl.cuda(), out=out,
+                  cache_row_index=None if index is None else index.cuda())
+    torch.cuda.synchronize()
+    got = out.float().cpu()
+    case = dict(B=B, S=S, C=C, Hq=Hq, Hkv=Hkv, pl=pl.tolist(), sl=sl.tolist(), indexed=index is not None)
+    rows = []
+    for b in range(B):
+        n = int(sl[b])
+        if n:
+            rows += [[b, i, rng.randint(0, Hq - 1)] for i in {0, n - 1, n // 2} | {rng.randint(0, n - 1) for _ in range(5)}]
+    if rows:
+        rows = torch.tensor(rows, dtype=torch.int32)
+        ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl, rows=rows)
+        sel = got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()]
+        assert (sel - ref).abs().max().item() <= 2e-2, case
+    for b in range(B):
+        assert torch.all(got[b, int(sl[b]):] == 123.0), case
+        assert not torch.isnan(got[b, : int(sl[b])]).any(), case
+
+
+TRIALS = {"attention": (_attention_trial, 150), "long_suffix": (_long_suffix_trial, 60), "confidence": (_confidence_trial, 150),
           "commit": (_commit_trial, 150), "lm_head": (_lm_head_trial, 60), "scattered": (_scattered_trial, 100)}
 
 
