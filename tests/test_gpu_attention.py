@@ -281,6 +281,22 @@ def test_long_suffix_every_cache_to_suffix_switch_position(lsp, oracle, S, tail)
         assert not torch.isnan(got[b, : int(sl[b])]).any()
 
 
+def test_very_long_prefix(lsp, oracle):
+    """131 000 cached keys per sequence (4 094 key blocks: hundreds of turns of the ring, block counters and
+    stream pointers far beyond the workload sizes), ragged at both ends, one KV head shared by 64 query
+    heads; sampled rows against the oracle."""
+    w = W.scaled(W.C2, B=2, S=256, P=131072, C=131072, Hq=64, Hkv=1, D=128, seed=4242)
+    pl = torch.tensor([131000, 65537], dtype=torch.int32)
+    sl = torch.tensor([256, 201], dtype=torch.int32)
+    kv = W.make_layer_kv(w, 0, prefix_len=pl)
+    got = _run(lsp, kv, pl, sl)
+    rows = torch.tensor([[b, i, h] for b in range(2) for i in (0, 31, 100, int(sl[b]) - 1) for h in (0, 33, 63)], dtype=torch.int32)
+    ref = oracle.attention(**kv, prefix_len=pl, suffix_len=sl, rows=rows)
+    sel = got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()]
+    assert (sel - ref).abs().max().item() <= TOL["bf16"]
+    assert torch.all(got[1, 201:] == 123.0) and not torch.isnan(got[0]).any() and not torch.isnan(got[1, :201]).any()
+
+
 def test_strided_views_many_rows_sampled(lsp, oracle):
     """Q/K/V sliced out of one fused [B,S,Hq+2Hkv,D] buffer and a cache with padded
     rows, at a size that takes the long-suffix launch shape."""
