@@ -97,6 +97,21 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.lsp_lm_head_confidence_workspace_bytes(2, 300, 1000) == 2 * 300 * 4 * 16
 
 
+def test_measurement_helpers_and_flip_update_validate_on_the_host():
+    import paper_2603_05454_amd as lsp
+    L = lsp.lib()
+    buf = (ctypes.c_int32 * 64)()
+    p = ctypes.c_void_p((ctypes.addressof(buf) + 15) & ~15)
+    assert L.lsp_bench_read(None, ctypes.c_int64(64), 1, p, None) == -1
+    assert L.lsp_bench_read(p, ctypes.c_int64(48), 2, p, None) == -1 and b"evenly" in L.lsp_last_error()
+    assert L.lsp_bench_mfma(None, 1, 1, p, None) == -1
+    assert L.lsp_bench_mfma(p, 0, 1, p, None) == -1
+    odd = ctypes.c_void_p(p.value + 4)
+    assert L.lsp_bench_mfma(odd, 1, 1, p, None) == -1 and b"aligned" in L.lsp_last_error()
+    assert L.lsp_flip_update(None, 1, 4, 4, p, p, p, p, p, 0, 0, None, None) == -1 and b"null" in L.lsp_last_error()
+    assert L.lsp_flip_update(p, 0, 4, 4, p, p, p, p, p, 0, 0, None, None) == -1
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     import paper_2603_05454_amd as lsp
     monkeypatch.setattr(lsp, "_lib", None)
