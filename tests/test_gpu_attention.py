@@ -363,3 +363,29 @@ def test_all_layers_in_one_launch(lsp, oracle, cfg):
                 assert torch.all(got[b, int(sl[b]):] == 123.0)
         single = _run(lsp, L, pl, sl)
         assert (single - got).abs().max().item() <= 2 * TOL[w.dtype]      # both are within TOL of the oracle
+
+
+@pytest.mark.parametrize("S,Hq", [(40, 4), (160, 32)])
+def test_more_layers_than_one_launch_holds(lsp, oracle, S, Hq):
+    """35 layers: lsp_attn_step_layers issues them as a launch of 32 and a launch of 3 (the short-suffix
+    kernel and the long-suffix kernel); every layer has its own operands, the first, the 32nd, the 33rd
+    and the last are compared with the oracle, and every layer with the single-layer call."""
+    nl = 35
+    w = W.scaled(W.C2, B=8, S=S, P=96, C=128, Hq=Hq, Hkv=Hq // 2, D=128, seed=900 + S)
+    pl = torch.tensor([96, 0, 31, 64, 128, 5, 96, 33], dtype=torch.int32)
+    sl = torch.tensor([S, S - 7, 1, S, 0, S // 2, S, 9], dtype=torch.int32)
+    host = [W.make_layer_kv(w, l, prefix_len=pl) for l in range(nl)]
+    dev = [{k: v.cuda() for k, v in L.items()} for L in host]
+    outs = [torch.full(L["q"].shape, 123.0, dtype=L["q"].dtype, device="cuda") for L in dev]
+    table = lsp.AttnLayerTable(*[[L[k] for L in dev] for k in ("q", "k_suf", "v_suf", "k_cache", "v_cache")], outs)
+    lsp.attn_step_layers(table, pl.cuda(), sl.cuda())
+    torch.cuda.synchronize()
+    rows = torch.tensor([[b, i, h] for b in range(w.B) for i in {0, int(sl[b]) // 2, int(sl[b]) - 1} if int(sl[b]) > 0
+                         for h in (0, Hq - 1)], dtype=torch.int32)
+    for l in range(nl):
+        got = outs[l].float().cpu()
+        single = _run(lsp, host[l], pl, sl)
+        assert (single - got).abs().max().item() <= 2 * TOL["bf16"], l   # (one launch for all layers may pick another key split)
+        if l in (0, 31, 32, nl - 1):
+            ref = oracle.attention(**host[l], prefix_len=pl, suffix_len=sl, rows=rows)
+            assert (got[rows[:, 0].long(), rows[:, 1].long(), rows[:, 2].long()] - ref).abs().max().item() <= TOL["bf16"], l
