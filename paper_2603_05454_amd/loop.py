@@ -17,7 +17,7 @@ from . import (AttnLayerTable, LayerTable, LspError, attn_step_layers, commit, c
 def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
                 prefix_len, suffix_len, tokens, kv_layers=None, gen_len=None, run_attention=False,
                 poll=1, max_steps=100000, stop_after=None, observer=None, timed=False, commit_kw=None,
-                graph=False, lm_head_weight=None, flip_window=None, flip_trace=False):
+                graph=False, lm_head_weight=None, flip_window=None, flip_trace=False, state=None):
     """logits_fn(step, prefix_len) -> device logits [B,S,V].  prefix_len,
     suffix_len, tokens and the caches in kv_layers (list of dicts q?, k_suf,
     v_suf, k_cache, v_cache) are updated in place.
@@ -38,16 +38,31 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     flip_window: (lo, hi) committed positions of a sequence, inclusive, inside which its
     flips also count towards the mid-generation window of Section 4.3.4 (default: 25 %-75 %
     of the generation length).  flip_trace: keep every step's per-sequence counts.
+    state: the dict an earlier call returned under "state" (one that stop_after ended, or
+    whose tensors were saved and loaded back): the call then continues that generation -
+    same generation start, last-seen ids and flip counters, step numbers going on from
+    where it stopped - so that stopping and resuming walks exactly like one uninterrupted
+    call.  The sequence state itself (lengths, tokens, caches) is the caller's as always.
     A sequence that still has active positions but commits nothing (min_commit = 0, or its
     cache / token buffer is full) would never finish: the loop raises LspError instead.
-    Returns dict(steps, flips, flip_denominator, window_flips, window_denominator, committed
-    [, flip_trace: int32 [steps,B,2]][, lsp_ms, lsp_ms_steps])."""
+    Returns dict(steps, flips, flip_denominator, window_flips, window_denominator, committed,
+    state[, flip_trace: int32 [steps,B,2]][, lsp_ms, lsp_ms_steps]); steps, the flip counts
+    and committed are totals since the generation began (earlier calls included)."""
     dev = prefix_len.device
     B = prefix_len.shape[0]
     G = int(gen_len if gen_len is not None else suffix_len.max().item())
-    base = prefix_len.clone()
-    last_id = torch.full((B, G), -1, dtype=torch.int32, device=dev)
-    counters = torch.zeros(4, dtype=torch.int64, device=dev)
+    if state is None:
+        base = prefix_len.clone()
+        last_id = torch.full((B, G), -1, dtype=torch.int32, device=dev)
+        counters = torch.zeros(4, dtype=torch.int64, device=dev)
+        steps = 0
+    else:
+        base, last_id, counters, steps = state["base"], state["last_id"], state["counters"], int(state["steps"])
+        if (tuple(base.shape) != (B,) or base.dtype != prefix_len.dtype or tuple(last_id.shape) != (B, G)
+                or last_id.dtype != torch.int32 or tuple(counters.shape) != (4,) or counters.dtype != torch.int64
+                or any(t.device != dev for t in (base, last_id, counters)) or steps < 0):
+            raise LspError("decode_loop: state does not belong to this batch (shapes, dtypes or device differ)")
+    first = steps
     if flip_window is None:
         flip_window = (-(-G // 4), (3 * G) // 4)
     step_counts = torch.zeros((B, 2), dtype=torch.int32, device=dev) if flip_trace else None
@@ -59,7 +74,6 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     if kv_layers is not None:
         table = LayerTable([L["k_suf"] for L in kv_layers], [L["v_suf"] for L in kv_layers],
                            [L["k_cache"] for L in kv_layers], [L["v_cache"] for L in kv_layers])
-    steps = 0
     out = conf = None
     attn_out = None
     events = []
@@ -86,7 +100,7 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
                      **(commit_kw or {}))
 
     while True:
-        if steps % poll == 0:
+        if (steps - first) % poll == 0:
             if out is None:
                 left, stalled = int(suffix_len.max().item()), 0
             else:   # one transfer: positions left, and whether a sequence that has some committed nothing
@@ -96,7 +110,7 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
             if stalled and min_commit >= 1:
                 raise LspError(f"decode_loop: a sequence with active positions committed nothing at step {steps - 1} "
                                f"(status_flags {out['status_flags'].tolist()}): cache or token buffer full")
-        if stop_after is not None and steps >= stop_after:
+        if stop_after is not None and steps - first >= stop_after:
             break
         assert steps < max_steps
         z = logits_fn(steps, prefix_len)
@@ -106,14 +120,14 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
             elif z.data_ptr() != zbuf.data_ptr():
                 zbuf.copy_(z)
                 z = zbuf
-        if graph and steps >= 1 and step_graph is None:   # one-time set-up, not part of a step
+        if graph and steps - first >= 1 and step_graph is None:   # one-time set-up, not part of a step
             step_graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(step_graph):
                 one_step(zbuf)
         if timed:
             events.append((torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)))
             events[-1][0].record()
-        if graph and steps >= 1:
+        if graph and steps - first >= 1:
             step_graph.replay()
         else:
             one_step(z)
@@ -127,7 +141,7 @@ def decode_loop(logits_fn, bitmap, V, tau, window, min_commit, snap_enabled,
     c = counters.tolist()
     committed = int((prefix_len - base).sum().item())
     res = dict(steps=steps, flips=c[0], flip_denominator=c[1], window_flips=c[2], window_denominator=c[3],
-               committed=committed)
+               committed=committed, state=dict(base=base, last_id=last_id, counters=counters, steps=steps))
     if flip_trace:
         res["flip_trace"] = torch.stack(trace).cpu() if trace else torch.zeros((0, B, 2), dtype=torch.int32)
     if timed:

@@ -212,3 +212,59 @@ def test_c5_fixed_threshold_loop_to_termination_two_sequences(lsp, oracle):
     reads every active logits row of every step: about 80 G elements)."""
     got = _c5_loop_against_oracle(oracle, W.scaled(W.C5, B=2, layers=2), W.C5.tau, {})
     assert got["steps"] > 200
+
+
+@pytest.mark.parametrize("graph", [False, True])
+@pytest.mark.parametrize("cut", [1, 4])
+def test_stopped_and_resumed_loop_walks_like_an_uninterrupted_one(lsp, oracle, tmp_path, cut, graph):
+    """Checkpoint and resume: the loop is stopped after `cut` steps, everything it owns
+    (lengths, tokens, caches, and the flip bookkeeping it returns as "state") goes through
+    a file on the host into NEW device tensors, and a second call continues from there.
+    Steps, flip and window counts, tokens, lengths and caches must equal the oracle's
+    single uninterrupted run; the two calls' flip traces, put end to end, its trace."""
+    from paper_2603_05454_amd.loop import decode_loop as gpu_loop
+    G = 96
+    w = W.scaled(W.C5, B=3, S=G, V=4096, P=16, gen_len=G, C=16 + G, layers=2, Hq=2, Hkv=2, D=64)
+    _, bm = W.make_delimiters(w)
+    fn = lambda step, p: W.make_logits(w, step=step, prefix_len=p.cpu())[0]
+    pl, sl = W.make_lengths(w)
+    tokens = W.make_tokens(w, w.C)
+    lay = [W.make_layer_kv(w, l) for l in range(2)]
+    ref = decode_loop(fn, bm, w.V, 0.9, w.window, 1, 1, pl, sl, tokens, kv_layers=lay)
+    assert ref["steps"] > cut + 2
+
+    pl_g, sl_g = (t.cuda() for t in W.make_lengths(w))
+    tok_g = W.make_tokens(w, w.C).cuda()
+    lay_g = [{k: v.cuda() for k, v in W.make_layer_kv(w, l).items()} for l in range(2)]
+    kw = dict(kv_layers=lay_g, gen_len=G, run_attention=graph, graph=graph, flip_trace=True)
+    part = gpu_loop(lambda s, p: fn(s, p).cuda(), bm.cuda(), w.V, 0.9, w.window, 1, 1, pl_g, sl_g, tok_g,
+                    stop_after=cut, **kw)
+    assert part["steps"] == cut and int(sl_g.max()) > 0
+    torch.save(dict(pl=pl_g, sl=sl_g, tok=tok_g, lay=lay_g, state=part["state"]), tmp_path / "ckpt.pt")
+    del pl_g, sl_g, tok_g, lay_g
+    ck = torch.load(tmp_path / "ckpt.pt", map_location="cpu", weights_only=True)
+    pl_g, sl_g, tok_g = ck["pl"].cuda(), ck["sl"].cuda(), ck["tok"].cuda()
+    lay_g = [{k: v.cuda() for k, v in L.items()} for L in ck["lay"]]
+    state = {k: (v.cuda() if torch.is_tensor(v) else v) for k, v in ck["state"].items()}
+    kw["kv_layers"] = lay_g
+    got = gpu_loop(lambda s, p: fn(s, p).cuda(), bm.cuda(), w.V, 0.9, w.window, 1, 1, pl_g, sl_g, tok_g,
+                   state=state, **kw)
+    got["flip_trace"] = torch.cat([part["flip_trace"], got["flip_trace"]])
+    _same_counts(got, ref)
+    assert torch.equal(tok_g.cpu(), tokens) and torch.equal(pl_g.cpu(), pl) and torch.equal(sl_g.cpu(), sl)
+    for Lg, Lr in zip(lay_g, lay):
+        assert torch.equal(Lg["k_cache"].cpu().view(torch.int16), Lr["k_cache"].view(torch.int16))
+        assert torch.equal(Lg["v_cache"].cpu().view(torch.int16), Lr["v_cache"].view(torch.int16))
+
+
+def test_state_of_another_batch_is_refused(lsp):
+    from paper_2603_05454_amd.loop import decode_loop as gpu_loop
+    G = 32
+    w = W.scaled(W.C5, B=2, S=G, V=512, P=4, gen_len=G, C=4 + G, layers=1, Hq=2, Hkv=2, D=64)
+    _, bm = W.make_delimiters(w)
+    pl_g, sl_g = (t.cuda() for t in W.make_lengths(w))
+    tok_g = W.make_tokens(w, w.C).cuda()
+    bad = dict(base=pl_g.clone(), last_id=torch.full((w.B, G + 1), -1, dtype=torch.int32, device="cuda"),
+               counters=torch.zeros(4, dtype=torch.int64, device="cuda"), steps=0)
+    with pytest.raises(lsp.LspError, match="state does not belong"):
+        gpu_loop(lambda s, p: None, bm.cuda(), w.V, 0.9, w.window, 1, 1, pl_g, sl_g, tok_g, gen_len=G, state=bad)
