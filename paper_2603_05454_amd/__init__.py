@@ -97,12 +97,49 @@ def _dev(*ts):
             raise LspError("liblsp takes device tensors only")
 
 
+def _need(name, t, dtype, shape=None, optional=False):
+    """A tensor whose element type the library cannot see through a plain pointer: the
+    wrong type or shape here would make a kernel read lengths or indices that are not
+    there, so it is refused before anything is launched."""
+    if t is None:
+        if optional:
+            return
+        raise LspError(f"{name} is required")
+    if t.dtype != dtype:
+        raise LspError(f"{name} must be {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise LspError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    if not t.is_contiguous():
+        raise LspError(f"{name} must be contiguous")
+
+
+def _need_kv(q, k_suf, v_suf, k_cache, v_cache, out):
+    B, S, Hq, D = q.shape
+    Hkv, C = k_suf.shape[2], k_cache.shape[1]
+    for name, t, shape in (("k_suf", k_suf, (B, S, Hkv, D)), ("v_suf", v_suf, (B, S, Hkv, D)),
+                           ("k_cache", k_cache, (B, C, Hkv, D)), ("v_cache", v_cache, (B, C, Hkv, D)),
+                           ("out", out, (B, S, Hq, D))):
+        if t.dtype != q.dtype or tuple(t.shape) != shape:
+            raise LspError(f"{name} must be {q.dtype} {shape}, got {t.dtype} {tuple(t.shape)}")
+    if v_suf.stride() != k_suf.stride() or v_cache.stride() != k_cache.stride():
+        raise LspError("K and V must share strides")
+
+
+def _need_conf_out(out, B, S):
+    if len(out) != 3:
+        raise LspError("out must be (top1_id, top1_prob, margin)")
+    _need("out[0] (top1_id)", out[0], torch.int32, (B, S))
+    _need("out[1] (top1_prob)", out[1], torch.float32, (B, S))
+    _need("out[2] (margin)", out[2], torch.float32, (B, S))
+
+
 def version() -> str:
     return lib().lsp_version().decode()
 
 
 def _strides3(t):
-    assert t.stride(3) == 1, "innermost dimension must be contiguous"
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise LspError("attention operands are [batch, row, head, D] with a contiguous innermost dimension")
     return (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
 
 
@@ -117,15 +154,17 @@ def attn_step(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len, scale=0
     prefix_len/suffix_len int32 [B].  Returns out [B,S,Hq,D] (same dtype as q);
     rows >= suffix_len[b] are not written.  cache_row_index int32 [B,C] selects
     lsp_attn_step_gather (key t of the prefix is cache row cache_row_index[b,t])."""
-    _dev(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len, cache_row_index)
+    _dev(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len, cache_row_index, out)
     B, S, Hq, D = q.shape
     if out is None:
         out = torch.empty((B, S, Hq, D), dtype=q.dtype, device=q.device)
+    _need_kv(q, k_suf, v_suf, k_cache, v_cache, out)
+    _need("prefix_len", prefix_len, torch.int32, (B,))
+    _need("suffix_len", suffix_len, torch.int32, (B,))
     d = AttnDesc(dtype=_dtype(q), B=B, S=S, Hq=Hq, Hkv=k_suf.shape[2], D=D, C=k_cache.shape[1],
                  scale=float(scale))
     d.q_stride = _strides3(q)
     d.kv_suf_stride = _strides3(k_suf)
-    assert v_suf.stride() == k_suf.stride() and v_cache.stride() == k_cache.stride()
     d.cache_stride = _strides3(k_cache)
     d.o_stride = _strides3(out)
     need = lib().lsp_attn_workspace_bytes(ctypes.byref(d))
@@ -137,8 +176,7 @@ def attn_step(q, k_suf, v_suf, k_cache, v_cache, prefix_len, suffix_len, scale=0
                                  _ptr(v_cache), _ptr(prefix_len), _ptr(suffix_len), _ptr(out),
                                  _ptr(workspace), ctypes.c_size_t(wb), _stream())
     else:
-        assert cache_row_index.dtype == torch.int32 and cache_row_index.is_contiguous()
-        assert tuple(cache_row_index.shape) == (B, k_cache.shape[1])
+        _need("cache_row_index", cache_row_index, torch.int32, (B, k_cache.shape[1]))
         rc = lib().lsp_attn_step_gather(ctypes.byref(d), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_cache),
                                         _ptr(v_cache), _ptr(cache_row_index), _ptr(prefix_len),
                                         _ptr(suffix_len), _ptr(out), _ptr(workspace), ctypes.c_size_t(wb),
@@ -153,12 +191,14 @@ class AttnLayerTable:
 
     def __init__(self, q, k_suf, v_suf, k_cache, v_cache, out):
         n = len(q)
-        assert len(k_suf) == len(v_suf) == len(k_cache) == len(v_cache) == len(out) == n > 0
+        if not (len(k_suf) == len(v_suf) == len(k_cache) == len(v_cache) == len(out) == n > 0):
+            raise LspError("AttnLayerTable: one tensor of each kind per layer, at least one layer")
         for lst in (q, k_suf, v_suf, k_cache, v_cache, out):
             for t in lst:
                 _dev(t)
-                assert t.shape == lst[0].shape and t.stride() == lst[0].stride() and t.dtype == q[0].dtype
-        assert v_suf[0].stride() == k_suf[0].stride() and v_cache[0].stride() == k_cache[0].stride()
+                if t.shape != lst[0].shape or t.stride() != lst[0].stride() or t.dtype != q[0].dtype:
+                    raise LspError("AttnLayerTable: all layers must share shape, strides and element type")
+        _need_kv(q[0], k_suf[0], v_suf[0], k_cache[0], v_cache[0], out[0])
         Arr = ctypes.c_void_p * n
         self.n = n
         self.arrays = [Arr(*[t.data_ptr() for t in lst]) for lst in (q, k_suf, v_suf, k_cache, v_cache, out)]
@@ -176,6 +216,8 @@ def attn_step_layers(table: AttnLayerTable, prefix_len, suffix_len, scale=0.0, w
     """lsp_attn_step_layers: the attention of every layer of `table` in one launch.
     Returns the list of per-layer outputs (table.out)."""
     _dev(prefix_len, suffix_len)
+    _need("prefix_len", prefix_len, torch.int32, (table.desc.B,))
+    _need("suffix_len", suffix_len, torch.int32, (table.desc.B,))
     table.desc.scale = float(scale)
     need = lib().lsp_attn_workspace_bytes(ctypes.byref(table.desc))
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
@@ -197,11 +239,15 @@ def confidence(logits, suffix_len=None, out=None, workspace=None):
     """lsp_confidence: logits [B,S,V] -> (top1_id int32, top1_prob f32, margin f32), [B,S]."""
     _dev(logits, suffix_len)
     B, S, V = logits.shape
-    assert logits.stride(2) == 1
+    if logits.stride(2) != 1:
+        raise LspError("logits rows must be contiguous")
     if out is None:
         out = (torch.empty((B, S), dtype=torch.int32, device=logits.device),
                torch.empty((B, S), dtype=torch.float32, device=logits.device),
                torch.empty((B, S), dtype=torch.float32, device=logits.device))
+    _dev(*out)
+    _need_conf_out(out, B, S)
+    _need("suffix_len", suffix_len, torch.int32, (B,), optional=True)
     need = lib().lsp_confidence_workspace_bytes(B, S, V)
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=logits.device)
@@ -219,7 +265,10 @@ def confidence_static(logits, suffix_len, out):
     allocation; `out` = (top1_id int32, top1_prob f32, margin f32), [B,S], is required."""
     _dev(logits, suffix_len, *out)
     B, S, V = logits.shape
-    assert logits.stride(2) == 1
+    if logits.stride(2) != 1:
+        raise LspError("logits rows must be contiguous")
+    _need_conf_out(out, B, S)
+    _need("suffix_len", suffix_len, torch.int32, (B,), optional=True)
     rc = lib().lsp_confidence_static(_dtype(logits), _ptr(logits), B, S, V,
                                      ctypes.c_int64(logits.stride(1)), ctypes.c_int64(logits.stride(0)),
                                      _ptr(suffix_len), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream())
@@ -238,11 +287,17 @@ def lm_head_confidence(hidden, weight, suffix_len=None, out=None, workspace=None
     _dev(hidden, weight, suffix_len)
     B, S, K = hidden.shape
     V = weight.shape[0]
-    assert weight.shape[1] == K and hidden.stride(2) == 1 and weight.stride(1) == 1
+    if weight.dim() != 2 or weight.shape[1] != K or weight.dtype != hidden.dtype:
+        raise LspError(f"weight must be {hidden.dtype} [V, {K}], got {weight.dtype} {tuple(weight.shape)}")
+    if hidden.stride(2) != 1 or weight.stride(1) != 1:
+        raise LspError("hidden and weight rows must be contiguous")
     if out is None:
         out = (torch.empty((B, S), dtype=torch.int32, device=hidden.device),
                torch.empty((B, S), dtype=torch.float32, device=hidden.device),
                torch.empty((B, S), dtype=torch.float32, device=hidden.device))
+    _dev(*out)
+    _need_conf_out(out, B, S)
+    _need("suffix_len", suffix_len, torch.int32, (B,), optional=True)
     need = lib().lsp_lm_head_confidence_workspace_bytes(B, S, V)
     if workspace is None or workspace.numel() * workspace.element_size() < need:
         workspace = torch.empty(need, dtype=torch.uint8, device=hidden.device)
@@ -261,17 +316,24 @@ class LayerTable:
 
     def __init__(self, k_suf, v_suf, k_cache, v_cache):
         n = len(k_suf)
-        assert len(v_suf) == len(k_cache) == len(v_cache) == n
+        if not (len(v_suf) == len(k_cache) == len(v_cache) == n > 0):
+            raise LspError("LayerTable: one tensor of each kind per layer, at least one layer")
         for lst in (k_suf, v_suf, k_cache, v_cache):
             for t in lst:
                 _dev(t)
-                assert t.is_contiguous() or (t.stride(3) == 1 and t.stride(2) == t.shape[3]
-                                             and t.stride(1) == t.shape[2] * t.shape[3])
+                if t.dim() != 4 or t.dtype != k_suf[0].dtype or t.shape != lst[0].shape or t.stride() != lst[0].stride():
+                    raise LspError("LayerTable: all layers must share shape, strides and element type")
+                if not (t.is_contiguous() or (t.stride(3) == 1 and t.stride(2) == t.shape[3]
+                                              and t.stride(1) == t.shape[2] * t.shape[3])):
+                    raise LspError("LayerTable: the rows of a sequence must be dense (only the batch stride is free)")
+        if k_cache[0].shape[0] != k_suf[0].shape[0] or k_cache[0].shape[2:] != k_suf[0].shape[2:]:
+            raise LspError("LayerTable: caches and suffix buffers disagree on batch, heads or head size")
         Arr = ctypes.c_void_p * n
         self.n = n
         self.arrays = [Arr(*[t.data_ptr() for t in lst]) for lst in (k_suf, v_suf, k_cache, v_cache)]
         self.keep = (k_suf, v_suf, k_cache, v_cache)
         self.kv_dtype = _dtype(k_suf[0])
+        self.B = k_suf[0].shape[0]
         self.S, self.Hkv, self.D = k_suf[0].shape[1:]
         self.C = k_cache[0].shape[1]
         self.suf_bs = k_suf[0].stride(0)
@@ -287,21 +349,37 @@ def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
     _dev(margin, top1_id, bitmap, prefix_len, suffix_len, tokens)
     B, S = margin.shape
     dev = margin.device
+    _need("margin", margin, torch.float32, (B, S))
+    _need("top1_id", top1_id, torch.int32, (B, S))
+    _need("bitmap", bitmap, torch.int32)
+    if bitmap.numel() < (int(V) + 31) // 32:
+        raise LspError(f"bitmap holds {bitmap.numel()} words, V = {V} needs {(int(V) + 31) // 32}")
+    _need("prefix_len", prefix_len, torch.int32, (B,))
+    _need("suffix_len", suffix_len, torch.int32, (B,))
+    if tokens is not None:
+        _need("tokens", tokens, torch.int32, (B, tokens.shape[1]) if tokens.dim() == 2 else (B, -1))
     if out is None:
         out = {"stable_mask": torch.empty((B, S), dtype=torch.uint8, device=dev)}
         for k in ("raw_boundary", "snapped_boundary", "commit_len", "status_flags"):
             out[k] = torch.empty(B, dtype=torch.int32, device=dev)
         out["tau_used"] = torch.empty(B, dtype=torch.float32, device=dev)
+    _dev(*out.values())
+    _need("out['stable_mask']", out["stable_mask"], torch.uint8, (B, S))
+    for k in ("raw_boundary", "snapped_boundary", "commit_len", "status_flags"):
+        _need(f"out['{k}']", out[k], torch.int32, (B,))
+    _need("out['tau_used']", out.get("tau_used"), torch.float32, (B,), optional=True)
     d = CommitDesc(B=B, S=S, V=V, tau=float(tau), window=int(window), min_commit=int(min_commit),
                    snap_enabled=int(snap_enabled), T=0 if tokens is None else tokens.shape[1],
                    adaptive=int(bool(adaptive)), alpha=float(alpha), beta=float(beta), max_commit=int(max_commit))
     if layers is not None:
-        assert layers.S == S
+        if layers.S != S or layers.B != B:
+            raise LspError(f"layers hold [{layers.B}, {layers.S}] suffix rows, margin is [{B}, {S}]")
         d.kv_dtype, d.Hkv, d.D, d.C, d.num_layers = layers.kv_dtype, layers.Hkv, layers.D, layers.C, layers.n
         d.suf_batch_stride, d.cache_batch_stride = layers.suf_bs, layers.cache_bs
         arrs = layers.arrays
     else:
-        assert C is not None
+        if C is None:
+            raise LspError("commit without layers needs the cache capacity C")
         d.C, d.num_layers = C, 0
         arrs = [ctypes.c_void_p(0)] * 4
     rc = lib().lsp_commit(ctypes.byref(d), _ptr(margin), _ptr(top1_id), _ptr(bitmap),
@@ -320,7 +398,13 @@ def flip_update(top1_id, prefix_len, suffix_len, base_prefix_len, last_id, count
     step_counts int32 [B,2], when given, receives this call's per-sequence counts."""
     _dev(top1_id, prefix_len, suffix_len, base_prefix_len, last_id, counters, step_counts)
     B, S = top1_id.shape
-    assert counters.numel() == 4 and counters.dtype == torch.int64
+    _need("top1_id", top1_id, torch.int32, (B, S))
+    _need("prefix_len", prefix_len, torch.int32, (B,))
+    _need("suffix_len", suffix_len, torch.int32, (B,))
+    _need("base_prefix_len", base_prefix_len, torch.int32, (B,))
+    _need("last_id", last_id, torch.int32, (B, last_id.shape[1]) if last_id.dim() == 2 else (B, -1))
+    _need("counters", counters, torch.int64, (4,))
+    _need("step_counts", step_counts, torch.int32, (B, 2), optional=True)
     lo, hi = (1, 0) if window is None else window
     rc = lib().lsp_flip_update(_ptr(top1_id), B, S, last_id.shape[1], _ptr(prefix_len), _ptr(suffix_len),
                                _ptr(base_prefix_len), _ptr(last_id), _ptr(counters), int(lo), int(hi),
@@ -336,6 +420,12 @@ def select_scattered(margin, suffix_len, count, out=None):
     if out is None:
         out = (torch.empty((B, S), dtype=torch.int32, device=margin.device),
                torch.empty((B, S), dtype=torch.uint8, device=margin.device))
+    _dev(*out)
+    _need("margin", margin, torch.float32, (B, S))
+    _need("suffix_len", suffix_len, torch.int32, (B,))
+    _need("count", count, torch.int32, (B,))
+    _need("out[0] (sel_index)", out[0], torch.int32, (B, S))
+    _need("out[1] (sel_mask)", out[1], torch.uint8, (B, S))
     rc = lib().lsp_select_scattered(_ptr(margin), B, S, _ptr(suffix_len), _ptr(count), _ptr(out[0]),
                                     _ptr(out[1]), _stream())
     _check(rc, "lsp_select_scattered")
@@ -347,9 +437,14 @@ def kv_gather_append(sel_index, count, prefix_len, layers: LayerTable, appended=
     for every layer of `layers`; prefix_len advanced in place.  Returns appended int32 [B]."""
     _dev(sel_index, count, prefix_len, appended)
     B, S = sel_index.shape
-    assert S == layers.S
+    if layers.S != S or layers.B != B:
+        raise LspError(f"layers hold [{layers.B}, {layers.S}] suffix rows, sel_index is [{B}, {S}]")
     if appended is None:
         appended = torch.empty(B, dtype=torch.int32, device=sel_index.device)
+    _need("sel_index", sel_index, torch.int32, (B, S))
+    _need("count", count, torch.int32, (B,))
+    _need("prefix_len", prefix_len, torch.int32, (B,))
+    _need("appended", appended, torch.int32, (B,))
     a = layers.arrays
     rc = lib().lsp_kv_gather_append(layers.kv_dtype, B, S, layers.Hkv, layers.D, layers.C, layers.n,
                                     ctypes.c_int64(layers.suf_bs), ctypes.c_int64(layers.cache_bs),

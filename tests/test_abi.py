@@ -118,3 +118,47 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(lsp, "LIB_PATH", "/nonexistent/liblsp.so")
     with pytest.raises(lsp.LspError):
         lsp.lib()
+
+
+def test_binding_refuses_tensors_of_the_wrong_type_or_shape(monkeypatch):
+    """Element types and shapes do not cross a boundary of plain pointers: the binding checks
+    what a kernel would otherwise misread (int64 lengths read as int32, a short index list,
+    K and V of different element types) and raises before it touches the library.  (Host
+    tensors stand in for device tensors here: the device check is switched off, and a call
+    that got past the checks would fail the test by reaching the library without a GPU.)"""
+    import torch
+    import paper_2603_05454_amd as m
+    monkeypatch.setattr(m, "_dev", lambda *ts: None)
+    monkeypatch.setattr(m, "lib", lambda: pytest.fail("the call reached the library"))
+    B, S, V = 2, 8, 64
+    i32 = lambda *shape: torch.zeros(shape, dtype=torch.int32)
+    f32 = lambda *shape: torch.zeros(shape, dtype=torch.float32)
+    good_out = (i32(B, S), f32(B, S), f32(B, S))
+    bm = i32(2)
+    cases = [
+        ("suffix_len must be torch.int32", lambda: m.confidence(f32(B, S, V), torch.zeros(B, dtype=torch.int64), out=good_out)),
+        ("top1_id", lambda: m.confidence(f32(B, S, V), None, out=(torch.zeros((B, S), dtype=torch.int64), f32(B, S), f32(B, S)))),
+        ("shape", lambda: m.confidence(f32(B, S, V), None, out=(i32(B, S + 1), f32(B, S), f32(B, S)))),
+        ("contiguous", lambda: m.confidence(f32(B, S, V), None, out=(i32(S, B).t(), f32(B, S), f32(B, S)))),
+        ("margin must be torch.float32", lambda: m.commit(f32(B, S).double(), i32(B, S), bm, V, 0.9, 4, 1, 1, i32(B), i32(B), C=16)),
+        ("top1_id must be torch.int32", lambda: m.commit(f32(B, S), i32(B, S).long(), bm, V, 0.9, 4, 1, 1, i32(B), i32(B), C=16)),
+        ("prefix_len must be torch.int32", lambda: m.commit(f32(B, S), i32(B, S), bm, V, 0.9, 4, 1, 1, i32(B).long(), i32(B), C=16)),
+        ("bitmap holds 1 words", lambda: m.commit(f32(B, S), i32(B, S), i32(1), V, 0.9, 4, 1, 1, i32(B), i32(B), C=16)),
+        ("tokens must be torch.int32", lambda: m.commit(f32(B, S), i32(B, S), bm, V, 0.9, 4, 1, 1, i32(B), i32(B),
+                                                        tokens=torch.zeros((B, 16), dtype=torch.int64), C=16)),
+        ("needs the cache capacity", lambda: m.commit(f32(B, S), i32(B, S), bm, V, 0.9, 4, 1, 1, i32(B), i32(B))),
+        ("counters must be torch.int64", lambda: m.flip_update(i32(B, S), i32(B), i32(B), i32(B), i32(B, S), i32(4))),
+        ("last_id must be torch.int32", lambda: m.flip_update(i32(B, S), i32(B), i32(B), i32(B), i32(B, S).long(),
+                                                              torch.zeros(4, dtype=torch.int64))),
+        ("count must be torch.int32", lambda: m.select_scattered(f32(B, S), i32(B), i32(B).long())),
+        ("v_suf must be", lambda: m.attn_step(f32(B, S, 4, 64), f32(B, S, 2, 64), f32(B, S, 2, 64).bfloat16(),
+                                              f32(B, 16, 2, 64), f32(B, 16, 2, 64), i32(B), i32(B))),
+        ("k_cache must be", lambda: m.attn_step(f32(B, S, 4, 64), f32(B, S, 2, 64), f32(B, S, 2, 64),
+                                                f32(B, 16, 1, 64), f32(B, 16, 1, 64), i32(B), i32(B))),
+        ("prefix_len must be torch.int32", lambda: m.attn_step(f32(B, S, 4, 64), f32(B, S, 2, 64), f32(B, S, 2, 64),
+                                                               f32(B, 16, 2, 64), f32(B, 16, 2, 64), i32(B).long(), i32(B))),
+        ("weight must be", lambda: m.lm_head_confidence(f32(B, S, 32).bfloat16(), f32(V, 32))),
+    ]
+    for text, call in cases:
+        with pytest.raises(m.LspError, match=text):
+            call()
