@@ -16,7 +16,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
 
 def build(verbose: bool = False, jobs: int = 6) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    # the hand-scheduled attention loop is generated (csrc/gen_attn_pipe.py -> csrc/lsp_attn_pipe_loop.inc)
+    # the hand-scheduled attention loop is generated (csrc/gen_attn_pipe.py -> csrc/lsp_attn_pipe_loop.inc, lsp_attn_pipe_idle_loop.inc)
     subprocess.run([sys.executable, os.path.join(CSRC, "gen_attn_pipe.py")], check=True, stdout=subprocess.DEVNULL)
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)

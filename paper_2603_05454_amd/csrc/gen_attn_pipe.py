@@ -1,6 +1,8 @@
 #!/usr/bin/env python3
 """Generator of lsp_attn_pipe_loop.inc: the hand-scheduled block loop of the
-long-suffix bf16 attention kernel (head_dim 128) as one inline-asm statement.
+long-suffix bf16 attention kernel (head_dim 128) as one inline-asm statement,
+and of lsp_attn_pipe_idle_loop.inc, the loader-only loop that waves without an
+active query run beside it (generate_idle below).
 
 Why generated assembly: with compiler scheduling a wave issues the products of a
 32-key block as one burst (waiting on every LDS fragment read just before its
@@ -287,6 +289,47 @@ def generate():
     return E.lines
 
 
+def generate_idle():
+    """The loop of a wave none of whose 32 queries is active (the last tile of a suffix that
+    is not a multiple of 256 rows): its share of every block's loads, the waits and the
+    barriers of the loop above in the same order, and nothing else - the matrix pipe and the
+    vector ALU of its SIMD are left to the other wave."""
+    E = Emitter()
+    li, kp, vp, step, jn = SG["li"], SG["kp"], SG["vp"], SG["step"], SG["jn"]
+    E.e(f"s_mov_b32 s{SG['m0save']}, m0")
+    E.e(f"s_mov_b64 s[{kp}:{kp + 1}], %[kc]")
+    E.e(f"s_mov_b64 s[{vp}:{vp + 1}], %[vc]")
+    E.e(f"s_mov_b32 s{step}, %[cstep]")
+    E.e(f"s_mov_b32 s{li}, 0")
+    E.e(f"s_mov_b32 s{jn}, 0")
+    E.e("s_cmp_lt_u32 %[nc], %[nb]")
+    E.e(f"s_cselect_b32 s{SG['sw']}, %[nc], -1")
+    for t in range(LA):
+        load_block(E, t, f"p{t}")
+    E.e(f"s_waitcnt vmcnt({2 * (LA - 4)})")
+    E.e("s_barrier")
+    E.e(".Lloop_%=:")
+    for u in range(NS):
+        load_block(E, (u + LA) % NS, f"i{u}")
+        E.e(f"s_add_u32 s{jn}, s{jn}, 1")
+        E.e(f"s_cmp_lt_u32 s{jn}, %[nb]")
+        E.e("s_cbranch_scc0 .Lexit_%=")
+        if u & 1:
+            E.e(f"s_waitcnt vmcnt({2 * (LA - 4)})")
+            E.e("s_barrier")
+    E.e("s_branch .Lloop_%=")
+    E.e(".Lexit_%=:")
+    E.e("s_waitcnt vmcnt(0)")
+    E.e(f"s_mov_b32 m0, s{SG['m0save']}")
+    E.e("s_branch .Lend_%=")
+    for u in range(NS):
+        switch_code(E, f"i{u}")
+    for t in range(LA):
+        switch_code(E, f"p{t}")
+    E.e(".Lend_%=:")
+    return E.lines
+
+
 HEADER = """// GENERATED by gen_attn_pipe.py - do not edit; the register map, the pipeline and the
 // synchronisation protocol are described in that script.
 // Expects in scope: f32x16 oacc[4]; float nm, lsum; u32x16 qf_lo, qf_hi, addr;
@@ -306,10 +349,31 @@ def main():
              '      [kc] "s"(kc_base), [vc] "s"(vc_base), [ks] "s"(ks_base), [vs] "s"(vs_base),\n'
              '      [cstep] "s"(cstep), [sstep] "s"(sstep), [nc] "s"(nc), [nb] "s"(nb), [ldsk] "s"(ldsk), [sc] "s"(sc)\n')
     text += "    : " + ", ".join(f'"{c}"' for c in clob) + ");\n"
-    out = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lsp_attn_pipe_loop.inc")
+    here = os.path.dirname(os.path.abspath(__file__))
+    out = os.path.join(here, "lsp_attn_pipe_loop.inc")
     with open(out, "w") as f:
         f.write(text)
+    with open(os.path.join(here, "lsp_attn_pipe_idle_loop.inc"), "w") as f:
+        f.write(idle_text())
     return out
+
+
+IDLE_HEADER = """// GENERATED by gen_attn_pipe.py - do not edit: the block loop of a wave without an active query
+// (loads, waits and barriers of lsp_attn_pipe_loop.inc in the same order, nothing else).
+// Expects in scope: u32x16 addr; uint64_t kc_base, vc_base, ks_base, vs_base;
+// uint32_t cstep, sstep, nc, nb, ldsk.
+"""
+
+
+def idle_text():
+    body = "\n".join(f'    "{l}\\n"' for l in generate_idle())
+    clob = [f"s{i}" for i in range(64, 80)] + ["scc", "memory"]
+    text = IDLE_HEADER + "asm volatile(\n" + body + "\n"
+    text += ('    : "+{v[152:167]}"(addr)\n'
+             '    : [kc] "s"(kc_base), [vc] "s"(vc_base), [ks] "s"(ks_base), [vs] "s"(vs_base),\n'
+             '      [cstep] "s"(cstep), [sstep] "s"(sstep), [nc] "s"(nc), [nb] "s"(nb), [ldsk] "s"(ldsk)\n')
+    text += "    : " + ", ".join(f'"{c}"' for c in clob) + ");\n"
+    return text
 
 
 if __name__ == "__main__":

@@ -44,7 +44,9 @@
 //    (gen_attn_pipe.py -> lsp_attn_pipe_loop.inc) in which the first product of
 //    block j+1, the soft-max of block j and the second product of block j are
 //    interleaved instruction by instruction; ragged first/last blocks and
-//    short sequences are handled in C++ around it.
+//    short sequences are handled in C++ around it.  A wave with no active
+//    query (last tile of a ragged suffix) runs lsp_attn_pipe_idle_loop.inc:
+//    its loads, waits and barriers only.
 #include "lsp_attn.h"
 
 namespace lsp {
@@ -1135,9 +1137,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const uint32_t nc_u = uint32_t(nc), nb = uint32_t(nc + ns);
     const uint32_t ldsk = lds0 + 1024u * uint32_t(wave_s);
     float nm = -mref;
-    {
+    if (q0 + 32 * wave_s < N) {
       const uint32_t nc = nc_u;  // (the name the generated statement uses)
 #include "lsp_attn_pipe_loop.inc"
+    } else {
+      // none of this wave's 32 queries is active (last tile of a suffix that is not a multiple of 256
+      // rows): it keeps its share of the loads and meets the others at the barriers, nothing else
+      const uint32_t nc = nc_u;
+#include "lsp_attn_pipe_idle_loop.inc"
     }
     mref = -nm;
   }

@@ -168,3 +168,69 @@ def test_the_checker_sees_a_missing_wait(lines):
         except AssertionError:
             caught += 1
     assert caught == len(waits[::3])
+
+
+# ---- the loop of a wave without an active query (csrc/lsp_attn_pipe_idle_loop.inc) ----
+
+def _sync_skeleton(lines):
+    """What the waves of a workgroup must agree on, in order, up to the loop's exit label: the
+    stage every load goes to (m0), the loads, the block counter and its exit test, the waits
+    for loads and the barriers."""
+    out = []
+    for l in lines:
+        if l == ".Lexit_%=:":
+            break
+        mnem, rest = _split(l)
+        if (mnem.startswith("global_load_lds") or mnem == "s_barrier" or "vmcnt" in l or l.endswith(":") and ("loop" in l or "issue" in l)
+                or mnem == "s_add_u32" and rest.startswith("m0") or "s72" in l or l == "s_cbranch_scc0 .Lexit_%="
+                or mnem in ("s_cmp_eq_u32", "s_cselect_b32", "s_addc_u32") or mnem == "s_add_u32" and rest.startswith(("s66", "s68", "s71"))
+                or mnem.startswith("s_cbranch_scc1")):
+            out.append(l)
+    return out
+
+
+def test_idle_include_is_what_the_generator_emits(gen):
+    with open(os.path.join(CSRC, "lsp_attn_pipe_idle_loop.inc")) as f:
+        text = f.read()
+    assert re.findall(r'^    "(.*)\\n"$', text, flags=re.M) == gen.generate_idle()
+
+
+def test_idle_loop_keeps_the_loads_waits_and_barriers_of_the_full_loop(gen, lines):
+    """A wave that runs the idle loop sits in the same workgroup as waves that run the full one:
+    both must issue the same loads into the same stages and meet at the same barriers, block by
+    block, or the ring protocol breaks (a stage overwritten while it is read, or a barrier that
+    some wave never reaches)."""
+    idle = gen.generate_idle()
+    a, b = _sync_skeleton(lines), _sync_skeleton(idle)
+    assert sum(l == "s_barrier" for l in a) == 1 + gen.NS // 2
+    assert sum(l.startswith("global_load_lds") for l in a) == 2 * (gen.LA + gen.NS)
+    assert a == b
+    # after the exit label: every load of the wave has landed before it goes on, m0 is restored
+    for stream in (lines, idle):
+        tail = stream[stream.index(".Lexit_%=:"):]
+        assert "vmcnt(0)" in tail[1] and any(l.startswith("s_mov_b32 m0") for l in tail[:4])
+    # the same cold cache -> suffix switch blocks exist
+    assert [l for l in idle if l.startswith(".Lswitch")] == [l for l in lines if l.startswith(".Lswitch")]
+    # the comparison notices a barrier, a load or a wait that one side lacks, and a load sent to another stage
+    for victim in ("s_barrier", "global_load_lds_dwordx4 v165, s[68:69]", "s_waitcnt vmcnt(4)"):
+        k = [i for i, l in enumerate(idle) if l == victim][3]
+        assert _sync_skeleton(idle[:k] + idle[k + 1:]) != a, victim
+    k = [i for i, l in enumerate(idle) if l.startswith("s_add_u32 m0")][5]
+    assert _sync_skeleton(idle[:k] + ["s_add_u32 m0, %[ldsk], 0"] + idle[k + 1:]) != a
+
+
+def test_idle_loop_leaves_the_matrix_pipe_and_the_vector_alu_alone(gen):
+    idle = gen.generate_idle()
+    labels = {l[:-1] for l in idle if l.endswith(":")}
+    for l in idle:
+        mnem, rest = _split(l)
+        assert not mnem.startswith(("v_mfma", "ds_", "v_exp", "v_fma", "v_max", "v_cvt", "v_dot")), l
+        assert not mnem.startswith(("s_store", "s_buffer_store", "s_atomic", "s_buffer_atomic", "s_dcache", "s_scratch_store")), l
+        if mnem.startswith("v_"):
+            assert mnem == "v_mov_b32" and _vregs(l) <= {gen.KOFF, gen.VOFF, gen.KOFF_S, gen.VOFF_S}, l
+        if mnem.startswith("global_load_lds"):
+            assert _vregs(l) <= {gen.KOFF, gen.VOFF}, l
+        for n in re.findall(r"vmcnt\((\d+)\)", l):
+            assert 0 <= int(n) <= 63, l
+        if mnem.startswith(("s_cbranch", "s_branch")):
+            assert rest.strip() in labels, l

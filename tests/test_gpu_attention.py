@@ -281,6 +281,20 @@ def test_long_suffix_every_cache_to_suffix_switch_position(lsp, oracle, S, tail)
         assert not torch.isnan(got[b, : int(sl[b])]).any()
 
 
+def test_long_suffix_last_tile_with_one_to_eight_active_waves(lsp, oracle):
+    """The last 256-query tile of a suffix that is not a multiple of 256 rows has waves with
+    no active query; they run the loader-only loop next to waves that run the full one.
+    Suffix lengths put 1..8 active waves into the last tile (a wave's 32 rows full, and cut
+    short by 5), over key streams whose cache part ends on both barrier parities; every active
+    row of every head is compared with the oracle, and rows beyond the suffix stay untouched."""
+    lens = [256 + 32 * k - d for k in range(1, 9) for d in (0, 5)] + [65, 96, 97, 255]
+    B = len(lens)
+    w = W.scaled(W.C2, B=B, S=512, P=200, C=224, Hq=2, Hkv=1, D=128, seed=909)
+    pl = torch.tensor([(200, 160, 131, 96)[b % 4] for b in range(B)], dtype=torch.int32)
+    sl = torch.tensor(lens, dtype=torch.int32)
+    _check_full(lsp, oracle, w, pl, sl)
+
+
 def test_very_long_prefix(lsp, oracle):
     """131 000 cached keys per sequence (4 094 key blocks: hundreds of turns of the ring, block counters and
     stream pointers far beyond the workload sizes), ragged at both ends, one KV head shared by 64 query
