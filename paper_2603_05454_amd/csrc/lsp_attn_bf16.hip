@@ -214,6 +214,9 @@ __device__ __forceinline__ void softmax_pv(f32x16 &s, f32x16 (&oacc)[D / 32], fl
 // together to share its K/V stream in L2.
 constexpr int kUnitGroup = 8;
 constexpr int kShortSuffix = 64;  // sequences with at most this many active rows take the key-split kernel
+// (the hand-scheduled kernel switches at 32: with its loader-only loop for waves without a query, a
+// tile with two active waves is faster than two key-split workgroups - 43 against 50 us per C5 layer)
+constexpr int kShortSuffixPipe = 32;
 struct Place {
   int b, g, h, q0;
   bool valid;
@@ -1038,7 +1041,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int P = min(max(a.prefix_len[b], 0), a.C);
   {  // sequences down to a few active rows: key-split mode, as in attn_bf16_ring_kernel
     const int tile = q0 / (32 * WM), QT = (a.S + 32 * WM - 1) / (32 * WM);
-    const int short_rows = 32 * min(QT, kShortSuffix / 32);
+    const int short_rows = 32 * min(QT, kShortSuffixPipe / 32);
     if (N <= short_rows) {
       if (32 * tile < N) key_split_body<D, 1, WM, false>(a, b, g, h, 32 * tile, N, P, smem);
       return;

@@ -71,7 +71,7 @@ def test_large_scores_and_moving_maximum(lsp, oracle, dtype, B, Hq, S):
     w = W.scaled(W.C2, dtype=dtype, B=B, S=S, P=200, C=256, Hq=Hq, Hkv=2, D=128, seed=91)
     pl = torch.full((B,), 200, dtype=torch.int32)
     sl = torch.full((B,), S, dtype=torch.int32)
-    sl[-1] = 40
+    sl[-1] = 30
     kv = W.make_layer_kv(w, 0, prefix_len=pl)
     dt = kv["q"].dtype
     ramp = torch.linspace(0.2, 6.0, 200).view(1, 200, 1, 1)
@@ -207,7 +207,7 @@ def test_mixed_short_and_long_suffixes_in_one_call(lsp, oracle):
     switch, in one call, sampled active rows against the oracle."""
     w = W.scaled(W.C2, B=8, S=320, P=200, C=256, Hq=16, Hkv=4, D=128, seed=77)
     pl = torch.tensor([200, 256, 0, 31, 200, 97, 256, 5], dtype=torch.int32)
-    sl = torch.tensor([0, 1, 33, 64, 65, 200, 320, 31], dtype=torch.int32)
+    sl = torch.tensor([0, 1, 33, 64, 65, 32, 320, 31], dtype=torch.int32)    # the switch sits at 32 / 33 (contiguous cache)
     kv = W.make_layer_kv(w, 0, prefix_len=pl)
     got = _run(lsp, kv, pl, sl)
     rows = torch.tensor([[b, i, h] for b in range(w.B) for i in range(int(sl[b])) for h in (0, 5, 15)
