@@ -736,6 +736,62 @@ def calibrate_read():
     print(json.dumps({"calibrate_read": res}))
 
 
+class BoardPower:
+    """Mean board power while a block of work runs: a host thread reads the GPU's hwmon sensor
+    (power1_average, else power1_input; microwatts) every 20 ms.  `watts` stays None when no
+    sensor is readable; `cap_watts` is the limit the driver enforces (power1_cap)."""
+
+    def __init__(self):
+        import glob
+        import torch
+        self.path = self.cap_watts = self.watts = None
+        want = None
+        try:
+            pr = torch.cuda.get_device_properties(0)
+            want = f"{pr.pci_domain_id:04x}:{pr.pci_bus_id:02x}:{pr.pci_device_id:02x}"
+        except Exception:
+            pass
+        cands = []
+        for d in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*")):
+            for name in ("power1_average", "power1_input"):
+                if os.path.exists(os.path.join(d, name)):
+                    cands.append((d, name))
+                    break
+        if want is not None and len(cands) > 1:
+            cands = [c for c in cands if want in os.path.realpath(c[0])] or cands
+        if cands:
+            self.path = os.path.join(*cands[0])
+            try:
+                self.cap_watts = int(open(os.path.join(cands[0][0], "power1_cap")).read()) / 1e6
+            except Exception:
+                pass
+
+    def __enter__(self):
+        import threading
+        self._stop = False
+        self._samples = []
+
+        def loop():
+            while not self._stop:
+                try:
+                    self._samples.append(int(open(self.path).read()))
+                except Exception:
+                    return
+                time.sleep(0.02)
+        self._thread = threading.Thread(target=loop, daemon=True) if self.path else None
+        if self._thread:
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        if self._thread:
+            self._thread.join()
+        if self._samples:
+            self.watts = round(sum(self._samples) / len(self._samples) / 1e6, 1)
+        return False
+
+
 def power_limit_probe(attention=True):
     """Why the matrix-bound kernel is priced against a peak it cannot be given: the chip lowers its
     clock under the power that toggling operands draw.  (1) A bare loop of the matrix instruction
@@ -764,18 +820,21 @@ def power_limit_probe(attention=True):
                 fn()
             torch.cuda.synchronize()
         total, n = 0.0, 0
-        while total < min_ms and n < 100:
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(burst):
-                fn()
-            b.record()
-            torch.cuda.synchronize()
-            total += a.elapsed_time(b)
-            n += 1
+        with BoardPower() as meter:
+            while total < min_ms and n < 100:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(burst):
+                    fn()
+                b.record()
+                torch.cuda.synchronize()
+                total += a.elapsed_time(b)
+                n += 1
+        power[0], power[1] = meter.watts, meter.cap_watts
         return total * 1e-3 / (n * burst)
 
     res = {}
+    power = [None, None]      # board power of the last timed() call, and the driver's limit
     n16 = lsp.MFMA_BENCH_OPERAND_BYTES // 2
     g = torch.Generator().manual_seed(5)
     iters, wgs = 100000, 256
@@ -786,6 +845,7 @@ def power_limit_probe(attention=True):
         ops = ops.to(dev)
         t = timed(lambda: lsp.bench_mfma(ops, iters, wgs, out))
         res["bare_mfma_loop_TFLOPs_" + name] = round(flop / t / 1e12, 1)
+        res["bare_mfma_loop_board_W_" + name] = power[0]
     if attention:
         w = W.scaled(W.C4, layers=2)
         pl, sl = W.make_lengths(w, device=dev)
@@ -801,15 +861,18 @@ def power_limit_probe(attention=True):
             t = timed(lambda: lsp.attn_step_layers(tab, pl, sl))
             res["attention_c4_us_per_layer_" + name] = round(t * 1e6 / 2, 1)
             res["attention_c4_TFLOPs_" + name] = round(fl / t / 1e12, 1)
+            res["attention_c4_board_W_" + name] = power[0]
             del tab, lay
             torch.cuda.empty_cache()
     if attention:
         for name in ("normal_0_1", "constant_0.5"):
             res["attention_over_bare_loop_" + name] = round(res["attention_c4_TFLOPs_" + name]
                                                             / res["bare_mfma_loop_TFLOPs_" + name], 3)
+    res["board_power_limit_W"] = power[1]
     res["note"] = ("identical instruction streams; only the operand values differ: with N(0,1) operands the chip runs the "
                    "matrix pipes at a lower clock to stay inside its power limit, so the bare loop on N(0,1) operands is "
-                   "the matrix ceiling this data allows (roofline.frac still uses the published 2500 TFLOP/s)")
+                   "the matrix ceiling this data allows (roofline.frac still uses the published 2500 TFLOP/s); board_W = mean of the "
+                   "GPU's hwmon power sensor over the timed launches, board_power_limit_W = the limit the driver enforces")
     return res
 
 
