@@ -234,3 +234,157 @@ def test_idle_loop_leaves_the_matrix_pipe_and_the_vector_alu_alone(gen):
             assert 0 <= int(n) <= 63, l
         if mnem.startswith(("s_cbranch", "s_branch")):
             assert rest.strip() in labels, l
+
+
+# ---- the ring protocol, by running the scalar skeleton of both loops on concrete block counts ----
+
+def _run_skeleton(lines, nb, nc, NS, max_steps=200000):
+    """Interpret the scalar instructions of a generated loop for a key stream of nc cache blocks
+    followed by nb - nc suffix blocks (vector, matrix and LDS instructions are skipped, the
+    rescale branch is never taken).  Returns the event list: ("load", which, stage, address),
+    ("wait", loads allowed to stay outstanding), ("barrier",), ("done", blocks finished)."""
+    labels = {l[:-1]: k for k, l in enumerate(lines) if l.endswith(":")}
+    KC, VC, KS, VS, CSTEP, SSTEP, LDSK = 0x10000000, 0x20000000, 0x30000000, 0x40000000, 0x8000, 0x2000, 0x400
+    sym = {"%[kc]": KC, "%[vc]": VC, "%[ks]": KS, "%[vs]": VS, "%[cstep]": CSTEP, "%[sstep]": SSTEP,
+           "%[nc]": nc, "%[nb]": nb, "%[ldsk]": LDSK}
+    reg = {"m0": 0}
+    scc = 0
+    M = 0xFFFFFFFF
+
+    def val(x):
+        x = x.strip()
+        if x in sym:
+            return sym[x]
+        m = re.fullmatch(r"s\[(\d+):(\d+)\]", x)
+        if m:
+            return reg[f"s{m.group(1)}"] | (reg[f"s{m.group(2)}"] << 32)
+        if x in reg or re.fullmatch(r"s\d+", x):
+            return reg[x]
+        return int(x, 0) & M
+
+    def signed(v):
+        return v - (1 << 32) if v & 0x80000000 else v
+
+    ev, i, steps = [], 0, 0
+    while i < len(lines):
+        steps += 1
+        assert steps < max_steps, "the loop does not end"
+        l = lines[i]
+        i += 1
+        if l.endswith(":"):
+            continue
+        mnem, rest = _split(l)
+        ops = [o.strip() for o in rest.split(",")] if rest else []
+        if mnem == "s_mov_b32":
+            reg[ops[0]] = val(ops[1]) & M
+        elif mnem == "s_mov_b64":
+            m = re.fullmatch(r"s\[(\d+):(\d+)\]", ops[0])
+            v = val(ops[1])
+            reg[f"s{m.group(1)}"], reg[f"s{m.group(2)}"] = v & M, v >> 32
+        elif mnem == "s_add_u32":
+            t = val(ops[1]) + val(ops[2])
+            reg[ops[0]], scc = t & M, int(t > M)
+        elif mnem == "s_addc_u32":
+            t = val(ops[1]) + val(ops[2]) + scc
+            reg[ops[0]], scc = t & M, int(t > M)
+        elif mnem == "s_sub_u32":
+            t = val(ops[1]) - val(ops[2])
+            reg[ops[0]], scc = t & M, int(t < 0)
+        elif mnem in ("s_cmp_lt_u32", "s_cmp_eq_u32", "s_cmp_lt_i32", "s_cmp_gt_i32"):
+            a, b = val(ops[0]), val(ops[1])
+            if mnem.endswith("i32"):
+                a, b = signed(a), signed(b)
+            scc = int({"lt": a < b, "eq": a == b, "gt": a > b}[mnem.split("_")[2]])
+        elif mnem == "s_cselect_b32":
+            reg[ops[0]] = (val(ops[1]) if scc else val(ops[2])) & M
+        elif mnem in ("s_cbranch_scc0", "s_cbranch_scc1"):
+            if scc == int(mnem[-1]):
+                i = labels[rest.strip()]
+        elif mnem == "s_cbranch_vccnz":
+            pass
+        elif mnem == "s_branch":
+            i = labels[rest.strip()]
+        elif mnem.startswith("global_load_lds"):
+            off = reg["m0"] - LDSK
+            ev.append(("load", "V" if off >= NS * 8192 else "K", (off % (NS * 8192)) // 8192, val(ops[1])))
+        elif mnem == "s_waitcnt":
+            m = re.search(r"vmcnt\((\d+)\)", l)
+            if m:
+                ev.append(("wait", int(m.group(1))))
+        elif mnem == "s_barrier":
+            ev.append(("barrier",))
+        else:
+            assert mnem.startswith(("v_", "ds_", "s_nop")), l
+    ev.append(("done", reg["s72"]))
+    return ev, (KC, VC, KS, VS, CSTEP, SSTEP)
+
+
+@pytest.mark.parametrize("which", ["full", "idle"])
+def test_ring_protocol_on_concrete_streams(gen, lines, which):
+    """For key streams of 1..40 blocks with the cache -> suffix switch at several places: block i is
+    requested, K and V, into stage (i mod NS) from the address of that block, in order; beyond the last
+    block the last one is requested again (so that the number of loads in flight stays what the waits
+    assume), LA blocks ahead of the iteration as everywhere else; at the barrier that ends iteration j
+    the wave has waited for its loads of every block up to j + 4 (those are read before the next
+    barrier) - at the first barrier up to block 3; a stage is not requested again before a barrier has
+    passed since the block it held was last read (V of block i is read in iteration i); and the loop
+    ends after exactly nb blocks."""
+    stream = lines if which == "full" else gen.generate_idle()
+    NS, LA = gen.NS, gen.LA
+    for nb in list(range(1, 41)):
+        for nc in sorted({0, 1, nb // 2, nb - 1, nb}):
+            ev, (KC, VC, KS, VS, CSTEP, SSTEP) = _run_skeleton(stream, nb, nc, NS)
+            assert ev[-1] == ("done", nb), (nb, nc, ev[-1])
+            loads = [e for e in ev if e[0] == "load"]
+            assert len(loads) == 2 * (LA + nb), (nb, nc, len(loads))      # LA before the loop, one per iteration
+            for i in range(LA + nb):
+                b = min(i, nb - 1)
+                k, v = loads[2 * i], loads[2 * i + 1]
+                ka, va = (KC + b * CSTEP, VC + b * CSTEP) if b < nc else (KS + (b - nc) * SSTEP, VS + (b - nc) * SSTEP)
+                assert k == ("load", "K", i % NS, ka) and v == ("load", "V", i % NS, va), (nb, nc, i, k, v)
+            issued = landed = barriers = 0
+            request_time = {}   # block -> number of barriers passed when it was requested
+            for e in ev:
+                if e[0] == "load":
+                    if e[1] == "K":
+                        request_time[issued // 2] = barriers
+                    issued += 1
+                elif e[0] == "wait":
+                    landed = max(landed, issued - e[1])
+                elif e[0] == "barrier":
+                    j = -1 if barriers == 0 else 2 * barriers - 1      # the iteration this barrier ends
+                    assert landed >= 2 * (j + 4 + 1), (nb, nc, "barrier", barriers, "landed", landed)
+                    barriers += 1
+            # barriers: one before the loop, then one after every odd iteration that is not the last
+            assert barriers == 1 + sum(1 for j in range(1, nb, 2) if j + 1 < nb), (nb, nc, barriers)
+            # block i (i >= NS) reuses the stage of block i - NS, last read in iteration i - NS; the barrier
+            # that ends odd iteration j is number (j + 1) / 2 + 1 counted from 1
+            for i in range(NS, LA + nb):
+                if i - NS >= nb:
+                    continue        # the stage held a repeat of the last block, which nobody reads
+                jodd = (i - NS) | 1
+                if jodd + 1 < nb:   # (that barrier exists; otherwise the loop has ended before the request)
+                    assert request_time[i] >= (jodd + 1) // 2 + 1, (nb, nc, i, request_time[i])
+
+
+def test_the_ring_check_sees_a_wait_that_is_too_lax(gen, lines):
+    """Planted mistake (on the CPU, in a copy of the text): the wait before the barriers made laxer by
+    one block must leave a needed block in flight."""
+    def first_violation(stream, nb):
+        ev, _ = _run_skeleton(stream, nb, 0, gen.NS)
+        issued = landed = barriers = 0
+        for e in ev:
+            if e[0] == "load":
+                issued += 1
+            elif e[0] == "wait":
+                landed = max(landed, issued - e[1])
+            elif e[0] == "barrier":
+                j = -1 if barriers == 0 else 2 * barriers - 1
+                if landed < 2 * (j + 4 + 1):
+                    return barriers
+                barriers += 1
+        return None
+
+    assert all(first_violation(lines, nb) is None for nb in range(1, 30))
+    lax = [("s_waitcnt vmcnt(6)" if l == "s_waitcnt vmcnt(4)" else l) for l in lines]
+    assert all(first_violation(lax, nb) == 0 for nb in range(1, 30))
