@@ -214,8 +214,9 @@ __device__ __forceinline__ void softmax_pv(f32x16 &s, f32x16 (&oacc)[D / 32], fl
 // together to share its K/V stream in L2.
 constexpr int kUnitGroup = 8;
 constexpr int kShortSuffix = 64;  // sequences with at most this many active rows take the key-split kernel
-// (the hand-scheduled kernel switches at 32: with its loader-only loop for waves without a query, a
-// tile with two active waves is faster than two key-split workgroups - 43 against 50 us per C5 layer)
+// (the hand-scheduled kernel decides per TILE and at 32 rows: with its loader-only loop for waves
+// without a query, a tile with two active waves is faster than two key-split workgroups - 38 against
+// 50 us per C5 layer - while a tile with one active wave is slower than one key-split workgroup)
 constexpr int kShortSuffixPipe = 32;
 struct Place {
   int b, g, h, q0;
@@ -1039,15 +1040,15 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int b = pl.b, g = pl.g, h = pl.h, q0 = pl.q0;
   const int N = min(max(a.suffix_len[b], 0), a.S);
   const int P = min(max(a.prefix_len[b], 0), a.C);
-  {  // sequences down to a few active rows: key-split mode, as in attn_bf16_ring_kernel
-    const int tile = q0 / (32 * WM), QT = (a.S + 32 * WM - 1) / (32 * WM);
-    const int short_rows = 32 * min(QT, kShortSuffixPipe / 32);
-    if (N <= short_rows) {
-      if (32 * tile < N) key_split_body<D, 1, WM, false>(a, b, g, h, 32 * tile, N, P, smem);
-      return;
-    }
-  }
   if (q0 >= N) return;
+  // A tile with at most 32 active rows - a sequence down to its last rows, or the tail of a longer
+  // suffix that ends just past a multiple of 256 - would keep seven waves idle for the whole key
+  // range: its one block of queries goes to the key-split body (as in attn_bf16_ring_kernel), which
+  // shares the KEY range between the eight waves instead.
+  if (N - q0 <= kShortSuffixPipe) {
+    key_split_body<D, 1, WM, false>(a, b, g, h, q0, N, P, smem);
+    return;
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int lq = lane & 31, hf = lane >> 5;
