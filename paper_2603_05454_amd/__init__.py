@@ -105,7 +105,7 @@ def _need(name, t, dtype, shape=None, optional=False):
         if optional:
             return
         raise LspError(f"{name} is required")
-    if t.dtype != dtype:
+    if t.dtype != dtype and not (isinstance(dtype, tuple) and t.dtype in dtype):
         raise LspError(f"{name} must be {dtype}, got {t.dtype}")
     if shape is not None and tuple(t.shape) != tuple(shape):
         raise LspError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
@@ -351,7 +351,7 @@ def commit(margin, top1_id, bitmap, V, tau, window, min_commit, snap_enabled,
     dev = margin.device
     _need("margin", margin, torch.float32, (B, S))
     _need("top1_id", top1_id, torch.int32, (B, S))
-    _need("bitmap", bitmap, torch.int32)
+    _need("bitmap", bitmap, (torch.int32, torch.uint32))     # 32 vocabulary ids per word, either way of naming the bits
     if bitmap.numel() < (int(V) + 31) // 32:
         raise LspError(f"bitmap holds {bitmap.numel()} words, V = {V} needs {(int(V) + 31) // 32}")
     _need("prefix_len", prefix_len, torch.int32, (B,))
