@@ -314,7 +314,7 @@ def _run_skeleton(lines, nb, nc, NS, max_steps=200000):
         elif mnem == "s_barrier":
             ev.append(("barrier",))
         else:
-            assert mnem.startswith(("v_", "ds_", "s_nop")), l
+            assert mnem.startswith(("v_", "ds_", "s_nop", "s_setprio")), l
     ev.append(("done", reg["s72"]))
     return ev, (KC, VC, KS, VS, CSTEP, SSTEP)
 
