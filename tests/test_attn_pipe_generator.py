@@ -388,3 +388,30 @@ def test_the_ring_check_sees_a_wait_that_is_too_lax(gen, lines):
     assert all(first_violation(lines, nb) is None for nb in range(1, 30))
     lax = [("s_waitcnt vmcnt(6)" if l == "s_waitcnt vmcnt(4)" else l) for l in lines]
     assert all(first_violation(lax, nb) == 0 for nb in range(1, 30))
+
+
+def test_wave_priority_is_back_to_default_wherever_the_statement_can_end(gen, lines):
+    """The loop raises the wave's priority for the first half of every iteration.  Walking the hot
+    path: the priority is 0 at every branch that can leave the loop (the exit test, and the cold
+    blocks, which come back to where they left), 1 exactly from the first S instruction to the
+    first O instruction of an iteration, and the loader-only loop never touches it."""
+    assert not any(l.startswith("s_setprio") for l in gen.generate_idle())
+    labels = {l[:-1]: k for k, l in enumerate(lines) if l.endswith(":")}
+    start, end = labels[".Lloop_%="], labels[".Lexit_%="]
+    prio, seen = 0, 0
+    for l in lines[:start]:
+        assert not l.startswith("s_setprio"), "the prologue runs at the default priority"
+    for l in lines[start:end]:
+        mnem, rest = _split(l)
+        if mnem == "s_setprio":
+            prio = int(rest)
+            assert prio in (0, 1)
+            seen += 1
+        elif mnem.startswith("s_cbranch") or mnem == "s_barrier":
+            assert prio == 0, l
+        elif mnem.startswith("v_mfma"):
+            writes_scores = _vregs(rest.split(",")[0]) <= set(range(0, 32))
+            assert prio == (1 if writes_scores else 0), l
+    assert seen == 2 * gen.NS and prio == 0
+    for l in lines[end:]:
+        assert not l.startswith("s_setprio"), "cold blocks and the exit leave the priority alone"
